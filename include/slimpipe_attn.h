@@ -1,0 +1,125 @@
+/*
+ * slimpipe_attn.h - C ABI of the slice-wise causal attention hot path for AMD MI355X (gfx950).
+ *
+ * The operation is the attention step of SlimPipe's slice-wise pipeline schedule
+ * (paper Sec. 4.1.2): the queries of slice i of a sequence attend causally to the cached
+ * keys/values of slices 0..i, forward and backward, the backward passes of the slices running
+ * in reverse order.  Any call may be restricted to a key range [kv_begin, kv_end); it then
+ * returns the partial output together with the softmax normaliser of that range, which is what
+ * the paper's attention context exchange (Sec. 4.2.2) and commutated context parallelism
+ * (Sec. 5) ship between devices and fold together "by the online softmax method".
+ *
+ * Conventions
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library allocates nothing on
+ *     the device, keeps no state between calls, enqueues its kernels on the caller's HIP stream
+ *     (a hipStream_t passed as void*, NULL = default stream) and returns without synchronising.
+ *   - q, out, d_out, dq:  [batch, s_q, n_q_heads, head_dim], element strides given, head_dim contiguous.
+ *   - k, v, dk_acc, dv_acc: [batch, kv_capacity, n_kv_heads, head_dim]; row j of the prefix IS global
+ *     key position j (the base pointer is position 0).
+ *   - lse: [batch, n_q_heads, s_q] float32, contiguous; lse = ln sum_j exp(scale * q.k_j) over the
+ *     visible keys of the call (natural log, scale inside).
+ *   - Key j is visible to query row r iff kv_begin <= j < kv_end and (causal == 0 or
+ *     j <= q_offset + r).  A row that sees no key gets out = 0, lse = -inf and contributes no
+ *     gradient.  An empty range is legal.
+ *   - Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - q, k, v, d_out are bf16.  All strides are in elements, must be multiples of 8 and the base
+ *     pointers 16-byte aligned.
+ *   - Every function returns SLIMPIPE_OK (0) or a negative slimpipe_status; nothing is printed,
+ *     nothing aborts.  Argument validation is pure host code.
+ */
+#ifndef SLIMPIPE_ATTN_H
+#define SLIMPIPE_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum slimpipe_status {
+  SLIMPIPE_OK = 0,
+  SLIMPIPE_EINVAL_NULL = -1,      /* a required pointer is NULL                                   */
+  SLIMPIPE_EINVAL_SHAPE = -2,     /* batch/s_q/heads <= 0, Hq % Hkv != 0, head_dim not 64 or 128,  */
+                                  /* scale not finite or <= 0, bad dtype code, n_parts out of range*/
+  SLIMPIPE_EINVAL_RANGE = -3,     /* kv_begin > kv_end, kv_end > kv_capacity, negative offsets     */
+  SLIMPIPE_EINVAL_STRIDE = -4,    /* a stride is not a positive multiple of 8 elements             */
+  SLIMPIPE_EINVAL_ALIGN = -5,     /* a pointer is not 16-byte aligned                              */
+  SLIMPIPE_EWORKSPACE = -6,       /* workspace missing or smaller than slimpipe_attn_workspace_bytes */
+  SLIMPIPE_ELAUNCH = -7           /* the HIP runtime refused a launch                              */
+} slimpipe_status;
+
+enum { SLIMPIPE_BF16 = 0, SLIMPIPE_F32 = 1 };
+
+typedef struct slimpipe_attn_params {
+  int32_t batch;
+  int32_t s_q;          /* rows of the query slice                                        */
+  int32_t n_q_heads;
+  int32_t n_kv_heads;
+  int32_t head_dim;     /* 64 or 128                                                      */
+  int32_t causal;       /* 0 or 1                                                         */
+  int64_t kv_capacity;  /* rows addressable behind k/v (and dk_acc/dv_acc)                */
+  int64_t q_offset;     /* global position of query row 0                                 */
+  int64_t kv_begin;     /* half-open range of global key positions this call attends to   */
+  int64_t kv_end;
+  float   scale;        /* softmax scale, > 0 (1/sqrt(head_dim) in every workload)        */
+  int32_t out_dtype;    /* forward: dtype of `out` (SLIMPIPE_BF16, or SLIMPIPE_F32 for    */
+                        /* partials that will be merged).  Ignored by backward.           */
+  int64_t q_stride_b, q_stride_s, q_stride_h;     /* q and dq                              */
+  int64_t kv_stride_b, kv_stride_s, kv_stride_h;  /* k, v, dk_acc, dv_acc                  */
+  int64_t o_stride_b, o_stride_s, o_stride_h;     /* out and d_out                         */
+} slimpipe_attn_params;
+
+/* Host-only argument check shared by every entry point (is_bwd != 0 also checks what only the
+ * backward needs).  No device access. */
+int slimpipe_attn_validate(const slimpipe_attn_params* p, int is_bwd);
+
+/* Bytes of device workspace the call needs (0 for forward; for backward one float per
+ * (batch, q head, row) for delta = rowsum(d_out * out), rounded up to 256 bytes). */
+int slimpipe_attn_workspace_bytes(const slimpipe_attn_params* p, int is_bwd, size_t* bytes);
+
+/* Forward of one query slice against keys [kv_begin, kv_end) of the cached prefix
+ * (Sec. 4.1.2; partial ranges: Sec. 4.2.2).  Writes out (dtype p->out_dtype, strides o_*) and
+ * lse [batch, n_q_heads, s_q].  Scores are never stored. */
+int slimpipe_attn_fwd(const slimpipe_attn_params* p,
+                      const void* q_slice, const void* k_prefix, const void* v_prefix,
+                      void* out, float* lse,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Backward of the same call (Sec. 4.1.2: backward per slice in reverse order, K/V kept for it).
+ *   out, lse : the rows' FINAL values (for a split computation: the merged ones), out is bf16.
+ *   dq       : dq_dtype SLIMPIPE_BF16 (overwritten) or SLIMPIPE_F32 (overwritten, or += when
+ *              dq_accumulate != 0, which is how the partial dq of several ranges are summed).
+ *              Uses the q strides.
+ *   dk_acc, dv_acc : float32 with the kv strides; rows [kv_begin, kv_end) are overwritten
+ *              (dkv_accumulate == 0) or incremented (!= 0); other rows are untouched.  Each row is
+ *              owned by one workgroup that sums queries and the heads of a GQA group in a fixed
+ *              order, so results are bit-reproducible from run to run.
+ * Enqueues: delta pre-pass, dq kernel, dk/dv kernel. */
+int slimpipe_attn_bwd(const slimpipe_attn_params* p,
+                      const void* q_slice, const void* k_prefix, const void* v_prefix,
+                      const void* out, const void* d_out, const float* lse,
+                      void* dq, int32_t dq_dtype, int32_t dq_accumulate,
+                      float* dk_acc, float* dv_acc, int32_t dkv_accumulate,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Online-softmax merge of n_parts (1..16) partial results over disjoint key sets (Sec. 4.2.2):
+ *   lse = ln sum_r exp(lse_r),  out = sum_r exp(lse_r - lse) * out_r   (weight 0 when lse_r = -inf).
+ * outs / lses are HOST arrays of n_parts DEVICE pointers.  Every partial out is contiguous
+ * [rows, n_q_heads, head_dim] of part_dtype, every partial lse [batch, n_q_heads, s_q] with
+ * rows = batch * s_q; the merged out has dtype out_dtype and the same contiguous layout. */
+int slimpipe_attn_merge(int32_t n_parts, const void* const* outs, const float* const* lses,
+                        int32_t part_dtype, int32_t batch, int32_t s_q, int32_t n_q_heads,
+                        int32_t head_dim, void* out, int32_t out_dtype, float* lse,
+                        void* hip_stream);
+
+/* Round float32 accumulators (dk_acc/dv_acc after the last slice's backward) to bf16, RNE.
+ * Contiguous, n_elems elements. */
+int slimpipe_attn_finalize_bf16(const float* acc, void* dst_bf16, int64_t n_elems, void* hip_stream);
+
+const char* slimpipe_attn_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLIMPIPE_ATTN_H */
