@@ -67,7 +67,8 @@ typedef struct slimpipe_attn_params {
                         /* partials that will be merged).  Ignored by backward.           */
   int64_t q_stride_b, q_stride_s, q_stride_h;     /* q and dq                              */
   int64_t kv_stride_b, kv_stride_s, kv_stride_h;  /* k, v, dk_acc, dv_acc                  */
-  int64_t o_stride_b, o_stride_s, o_stride_h;     /* out and d_out                         */
+  int64_t o_stride_b, o_stride_s, o_stride_h;     /* out                                   */
+  int64_t do_stride_b, do_stride_s, do_stride_h;  /* d_out (backward only)                 */
 } slimpipe_attn_params;
 
 /* Host-only argument check shared by every entry point (is_bwd != 0 also checks what only the

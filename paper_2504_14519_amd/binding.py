@@ -1,0 +1,171 @@
+"""ctypes binding of libslimpipe_attn.so: argument marshalling only.
+
+Same entry-point names as the C header.  Tensors are torch tensors on the GPU; torch supplies
+device memory and the current stream, every step of the computation runs in the library's kernels.
+There is no fallback: if the shared library is missing the import fails.
+"""
+import ctypes
+import math
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libslimpipe_attn.so")
+
+BF16, F32 = 0, 1
+
+
+class SlimpipeError(RuntimeError):
+    pass
+
+
+class AttnParams(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("s_q", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+        ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("causal", ctypes.c_int32),
+        ("kv_capacity", ctypes.c_int64), ("q_offset", ctypes.c_int64), ("kv_begin", ctypes.c_int64),
+        ("kv_end", ctypes.c_int64), ("scale", ctypes.c_float), ("out_dtype", ctypes.c_int32),
+        ("q_stride_b", ctypes.c_int64), ("q_stride_s", ctypes.c_int64), ("q_stride_h", ctypes.c_int64),
+        ("kv_stride_b", ctypes.c_int64), ("kv_stride_s", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64),
+        ("o_stride_b", ctypes.c_int64), ("o_stride_s", ctypes.c_int64), ("o_stride_h", ctypes.c_int64),
+        ("do_stride_b", ctypes.c_int64), ("do_stride_s", ctypes.c_int64), ("do_stride_h", ctypes.c_int64),
+    ]
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError("libslimpipe_attn.so is not built: run `python -m paper_2504_14519_amd.build` "
+                          "(there is no fallback path)")
+    L = ctypes.CDLL(_LIB_PATH)
+    P = ctypes.POINTER(AttnParams)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.slimpipe_attn_validate.argtypes = [P, ctypes.c_int]
+    L.slimpipe_attn_validate.restype = ctypes.c_int
+    L.slimpipe_attn_workspace_bytes.argtypes = [P, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
+    L.slimpipe_attn_workspace_bytes.restype = ctypes.c_int
+    L.slimpipe_attn_fwd.argtypes = [P, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.slimpipe_attn_fwd.restype = ctypes.c_int
+    L.slimpipe_attn_bwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, ctypes.c_size_t, vp]
+    L.slimpipe_attn_bwd.restype = ctypes.c_int
+    L.slimpipe_attn_merge.argtypes = [i32, ctypes.POINTER(vp), ctypes.POINTER(vp), i32, i32, i32, i32, i32, vp, i32, vp, vp]
+    L.slimpipe_attn_merge.restype = ctypes.c_int
+    L.slimpipe_attn_finalize_bf16.argtypes = [vp, vp, i64, vp]
+    L.slimpipe_attn_finalize_bf16.restype = ctypes.c_int
+    L.slimpipe_attn_strerror.argtypes = [ctypes.c_int]
+    L.slimpipe_attn_strerror.restype = ctypes.c_char_p
+    return L
+
+
+lib = _load()
+
+
+def slimpipe_attn_strerror(code):
+    return lib.slimpipe_attn_strerror(int(code)).decode()
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise SlimpipeError("%s failed: %d (%s)" % (what, rc, slimpipe_attn_strerror(rc)))
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _same_strides(a, b):
+    """Equal shapes and equal strides on every dimension longer than one."""
+    return a.shape == b.shape and all(sa == sb for n, sa, sb in zip(a.shape, a.stride(), b.stride()) if n > 1)
+
+
+def make_params(q, k, out_like, q_offset, kv_begin, kv_end, causal, scale, out_dtype=BF16):
+    """Fill the parameter block from tensor shapes/strides.  q [B,s,Hq,D], k [B,Nkv,Hkv,D]."""
+    B, s, Hq, D = q.shape
+    p = AttnParams()
+    p.batch, p.s_q, p.n_q_heads, p.n_kv_heads, p.head_dim = B, s, Hq, k.shape[2], D
+    p.causal = 1 if causal else 0
+    p.kv_capacity, p.q_offset, p.kv_begin, p.kv_end = k.shape[1], q_offset, kv_begin, kv_end
+    p.scale = float(scale) if scale is not None else 1.0 / math.sqrt(D)
+    p.out_dtype = out_dtype
+    p.q_stride_b, p.q_stride_s, p.q_stride_h = q.stride(0), q.stride(1), q.stride(2)
+    p.kv_stride_b, p.kv_stride_s, p.kv_stride_h = k.stride(0), k.stride(1), k.stride(2)
+    p.o_stride_b, p.o_stride_s, p.o_stride_h = out_like.stride(0), out_like.stride(1), out_like.stride(2)
+    return p
+
+
+def slimpipe_attn_validate(params, is_bwd=False):
+    return lib.slimpipe_attn_validate(ctypes.byref(params), 1 if is_bwd else 0)
+
+
+def slimpipe_attn_workspace_bytes(params, is_bwd):
+    n = ctypes.c_size_t(0)
+    _check(lib.slimpipe_attn_workspace_bytes(ctypes.byref(params), 1 if is_bwd else 0, ctypes.byref(n)), "workspace_bytes")
+    return n.value
+
+
+def slimpipe_attn_fwd(q_slice, k_prefix, v_prefix, q_offset, kv_begin, kv_end, causal=True, scale=None,
+                      out_dtype=BF16, out=None, lse=None):
+    """-> (out, lse).  out [B,s,Hq,D] (bf16 or fp32), lse [B,Hq,s] fp32."""
+    import torch
+    B, s, Hq, D = q_slice.shape
+    if out is None:
+        out = torch.empty((B, s, Hq, D), device=q_slice.device, dtype=torch.float32 if out_dtype == F32 else torch.bfloat16)
+    if lse is None:
+        lse = torch.empty((B, Hq, s), device=q_slice.device, dtype=torch.float32)
+    p = make_params(q_slice, k_prefix, out, q_offset, kv_begin, kv_end, causal, scale, out_dtype)
+    _check(lib.slimpipe_attn_fwd(ctypes.byref(p), q_slice.data_ptr(), k_prefix.data_ptr(), v_prefix.data_ptr(),
+                                 out.data_ptr(), lse.data_ptr(), None, 0, _stream()), "slimpipe_attn_fwd")
+    return out, lse
+
+
+def slimpipe_attn_bwd(q_slice, k_prefix, v_prefix, out, d_out, lse, q_offset, kv_begin, kv_end, dk_acc, dv_acc,
+                      causal=True, scale=None, dq=None, dq_dtype=BF16, dq_accumulate=False, dkv_accumulate=True,
+                      workspace=None):
+    """-> dq.  dk_acc/dv_acc (fp32, shaped like k_prefix) get rows [kv_begin, kv_end) written or incremented."""
+    import torch
+    if dq is None:
+        dq = torch.empty_like(q_slice, dtype=torch.float32 if dq_dtype == F32 else torch.bfloat16)
+    if not (_same_strides(dq, q_slice) and _same_strides(dk_acc, k_prefix) and _same_strides(dv_acc, k_prefix)):
+        raise SlimpipeError("dq must have the strides of q; dk_acc/dv_acc those of k")
+    p = make_params(q_slice, k_prefix, out, q_offset, kv_begin, kv_end, causal, scale)
+    p.do_stride_b, p.do_stride_s, p.do_stride_h = d_out.stride(0), d_out.stride(1), d_out.stride(2)
+    need = slimpipe_attn_workspace_bytes(p, True)
+    if workspace is None:
+        workspace = torch.empty(need, device=q_slice.device, dtype=torch.uint8)
+    _check(lib.slimpipe_attn_bwd(ctypes.byref(p), q_slice.data_ptr(), k_prefix.data_ptr(), v_prefix.data_ptr(),
+                                 out.data_ptr(), d_out.data_ptr(), lse.data_ptr(), dq.data_ptr(), dq_dtype,
+                                 1 if dq_accumulate else 0, dk_acc.data_ptr(), dv_acc.data_ptr(),
+                                 1 if dkv_accumulate else 0, workspace.data_ptr(), workspace.numel(), _stream()),
+           "slimpipe_attn_bwd")
+    return dq
+
+
+def slimpipe_attn_merge(outs, lses, out_dtype=BF16, out=None, lse=None):
+    """Merge partial (out, lse) pairs over disjoint key sets -> (out, lse)."""
+    import torch
+    n = len(outs)
+    B, s, Hq, D = outs[0].shape
+    part_dtype = F32 if outs[0].dtype == torch.float32 else BF16
+    for o in outs:
+        if not o.is_contiguous():
+            raise SlimpipeError("partial outputs must be contiguous")
+    if out is None:
+        out = torch.empty((B, s, Hq, D), device=outs[0].device, dtype=torch.float32 if out_dtype == F32 else torch.bfloat16)
+    if lse is None:
+        lse = torch.empty((B, Hq, s), device=outs[0].device, dtype=torch.float32)
+    op = (ctypes.c_void_p * n)(*[o.data_ptr() for o in outs])
+    lp = (ctypes.c_void_p * n)(*[l.data_ptr() for l in lses])
+    _check(lib.slimpipe_attn_merge(n, op, lp, part_dtype, B, s, Hq, D, out.data_ptr(), out_dtype, lse.data_ptr(), _stream()),
+           "slimpipe_attn_merge")
+    return out, lse
+
+
+def slimpipe_attn_finalize_bf16(acc, dst=None):
+    import torch
+    if dst is None:
+        dst = torch.empty(acc.shape, device=acc.device, dtype=torch.bfloat16)
+    _check(lib.slimpipe_attn_finalize_bf16(acc.data_ptr(), dst.data_ptr(), acc.numel(), _stream()), "finalize_bf16")
+    return dst

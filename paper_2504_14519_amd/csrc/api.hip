@@ -1,0 +1,173 @@
+// C ABI of the library: host-only validation, launch planning, error mapping.
+#include <math.h>
+#include <string.h>
+
+#include "../../include/slimpipe_attn.h"
+#include "kernels.hpp"
+
+using namespace slimpipe;
+
+namespace {
+
+bool stride_ok(int64_t s) { return s > 0 && (s % 8) == 0; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+size_t delta_bytes(const slimpipe_attn_params* p) {
+  size_t n = (size_t)p->batch * (size_t)p->n_q_heads * (size_t)p->s_q * sizeof(float);
+  return (n + 255) & ~(size_t)255;
+}
+
+}  // namespace
+
+extern "C" {
+
+int slimpipe_attn_validate(const slimpipe_attn_params* p, int is_bwd) {
+  if (!p) return SLIMPIPE_EINVAL_NULL;
+  if (p->batch <= 0 || p->s_q <= 0 || p->n_q_heads <= 0 || p->n_kv_heads <= 0) return SLIMPIPE_EINVAL_SHAPE;
+  if (p->n_q_heads % p->n_kv_heads != 0) return SLIMPIPE_EINVAL_SHAPE;
+  if (p->head_dim != 64 && p->head_dim != 128) return SLIMPIPE_EINVAL_SHAPE;
+  if (!(p->scale > 0.0f) || !isfinite(p->scale)) return SLIMPIPE_EINVAL_SHAPE;
+  if (p->causal != 0 && p->causal != 1) return SLIMPIPE_EINVAL_SHAPE;
+  if (p->out_dtype != SLIMPIPE_BF16 && p->out_dtype != SLIMPIPE_F32) return SLIMPIPE_EINVAL_SHAPE;
+  if (p->batch > 65535 || p->n_q_heads > 65535) return SLIMPIPE_EINVAL_SHAPE;   /* grid y/z limits */
+  if (p->kv_capacity < 0 || p->q_offset < 0 || p->kv_begin < 0) return SLIMPIPE_EINVAL_RANGE;
+  if (p->kv_begin > p->kv_end || p->kv_end > p->kv_capacity) return SLIMPIPE_EINVAL_RANGE;
+  if (p->q_offset > (int64_t)1 << 40 || p->kv_capacity > (int64_t)1 << 40) return SLIMPIPE_EINVAL_RANGE;
+  const int64_t s[9] = {p->q_stride_b, p->q_stride_s, p->q_stride_h, p->kv_stride_b, p->kv_stride_s,
+                        p->kv_stride_h, p->o_stride_b, p->o_stride_s, p->o_stride_h};
+  for (int i = 0; i < 9; ++i)
+    if (!stride_ok(s[i])) return SLIMPIPE_EINVAL_STRIDE;
+  if (is_bwd && (!stride_ok(p->do_stride_b) || !stride_ok(p->do_stride_s) || !stride_ok(p->do_stride_h) ||
+                 p->do_stride_h < p->head_dim))
+    return SLIMPIPE_EINVAL_STRIDE;
+  if (p->q_stride_h < p->head_dim || p->kv_stride_h < p->head_dim || p->o_stride_h < p->head_dim)
+    return SLIMPIPE_EINVAL_STRIDE;
+  return SLIMPIPE_OK;
+}
+
+int slimpipe_attn_workspace_bytes(const slimpipe_attn_params* p, int is_bwd, size_t* bytes) {
+  if (!bytes) return SLIMPIPE_EINVAL_NULL;
+  int rc = slimpipe_attn_validate(p, is_bwd);
+  if (rc != SLIMPIPE_OK) return rc;
+  *bytes = is_bwd ? delta_bytes(p) : 0;
+  return SLIMPIPE_OK;
+}
+
+int slimpipe_attn_fwd(const slimpipe_attn_params* p, const void* q_slice, const void* k_prefix,
+                      const void* v_prefix, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                      void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  int rc = slimpipe_attn_validate(p, 0);
+  if (rc != SLIMPIPE_OK) return rc;
+  if (!q_slice || !out || !lse) return SLIMPIPE_EINVAL_NULL;
+  if (p->kv_end > 0 && (!k_prefix || !v_prefix)) return SLIMPIPE_EINVAL_NULL;
+  if (!aligned16(q_slice) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(out) ||
+      (reinterpret_cast<uintptr_t>(lse) & 3u))
+    return SLIMPIPE_EINVAL_ALIGN;
+  FwdArgs a;
+  a.q = static_cast<const __bf16*>(q_slice);
+  a.k = static_cast<const __bf16*>(k_prefix);
+  a.v = static_cast<const __bf16*>(v_prefix);
+  a.out = out;
+  a.lse = lse;
+  a.s_q = p->s_q; a.n_q_heads = p->n_q_heads; a.group = p->n_q_heads / p->n_kv_heads;
+  a.causal = p->causal; a.out_f32 = (p->out_dtype == SLIMPIPE_F32);
+  a.q_offset = p->q_offset; a.kv_begin = p->kv_begin; a.kv_end = p->kv_end;
+  a.scale_log2e = p->scale * 1.4426950408889634f;
+  a.q_stride_b = p->q_stride_b; a.q_stride_s = p->q_stride_s; a.q_stride_h = p->q_stride_h;
+  a.kv_stride_b = p->kv_stride_b; a.kv_stride_s = p->kv_stride_s; a.kv_stride_h = p->kv_stride_h;
+  a.o_stride_b = p->o_stride_b; a.o_stride_s = p->o_stride_s; a.o_stride_h = p->o_stride_h;
+  hipError_t e = launch_fwd(a, p->batch, p->head_dim, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SLIMPIPE_OK : SLIMPIPE_ELAUNCH;
+}
+
+int slimpipe_attn_bwd(const slimpipe_attn_params* p, const void* q_slice, const void* k_prefix,
+                      const void* v_prefix, const void* out, const void* d_out, const float* lse, void* dq,
+                      int32_t dq_dtype, int32_t dq_accumulate, float* dk_acc, float* dv_acc,
+                      int32_t dkv_accumulate, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = slimpipe_attn_validate(p, 1);
+  if (rc != SLIMPIPE_OK) return rc;
+  if (!q_slice || !out || !d_out || !lse || !dq || !dk_acc || !dv_acc) return SLIMPIPE_EINVAL_NULL;
+  if (p->kv_end > 0 && (!k_prefix || !v_prefix)) return SLIMPIPE_EINVAL_NULL;
+  if (dq_dtype != SLIMPIPE_BF16 && dq_dtype != SLIMPIPE_F32) return SLIMPIPE_EINVAL_SHAPE;
+  if (dq_accumulate && dq_dtype != SLIMPIPE_F32) return SLIMPIPE_EINVAL_SHAPE;
+  if (!aligned16(q_slice) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(out) ||
+      !aligned16(d_out) || !aligned16(dq) || !aligned16(dk_acc) || !aligned16(dv_acc) ||
+      (reinterpret_cast<uintptr_t>(lse) & 3u))
+    return SLIMPIPE_EINVAL_ALIGN;
+  if (!workspace || workspace_bytes < delta_bytes(p)) return SLIMPIPE_EWORKSPACE;
+  if (!aligned16(workspace)) return SLIMPIPE_EINVAL_ALIGN;
+  BwdArgs a;
+  a.q = static_cast<const __bf16*>(q_slice);
+  a.k = static_cast<const __bf16*>(k_prefix);
+  a.v = static_cast<const __bf16*>(v_prefix);
+  a.out = static_cast<const __bf16*>(out);
+  a.d_out = static_cast<const __bf16*>(d_out);
+  a.lse = lse;
+  a.delta = static_cast<float*>(workspace);
+  a.dq = dq; a.dk_acc = dk_acc; a.dv_acc = dv_acc;
+  a.s_q = p->s_q; a.n_q_heads = p->n_q_heads; a.n_kv_heads = p->n_kv_heads;
+  a.group = p->n_q_heads / p->n_kv_heads; a.causal = p->causal;
+  a.dq_f32 = (dq_dtype == SLIMPIPE_F32); a.dq_accumulate = dq_accumulate ? 1 : 0;
+  a.dkv_accumulate = dkv_accumulate ? 1 : 0;
+  a.q_offset = p->q_offset; a.kv_begin = p->kv_begin; a.kv_end = p->kv_end;
+  a.scale = p->scale; a.scale_log2e = p->scale * 1.4426950408889634f;
+  a.q_stride_b = p->q_stride_b; a.q_stride_s = p->q_stride_s; a.q_stride_h = p->q_stride_h;
+  a.kv_stride_b = p->kv_stride_b; a.kv_stride_s = p->kv_stride_s; a.kv_stride_h = p->kv_stride_h;
+  a.o_stride_b = p->o_stride_b; a.o_stride_s = p->o_stride_s; a.o_stride_h = p->o_stride_h;
+  a.do_stride_b = p->do_stride_b; a.do_stride_s = p->do_stride_s; a.do_stride_h = p->do_stride_h;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (launch_delta(a, p->batch, p->head_dim, st) != hipSuccess) return SLIMPIPE_ELAUNCH;
+  if (launch_bwd_dq(a, p->batch, p->head_dim, st) != hipSuccess) return SLIMPIPE_ELAUNCH;
+  if (launch_bwd_dkdv(a, p->batch, p->head_dim, st) != hipSuccess) return SLIMPIPE_ELAUNCH;
+  return SLIMPIPE_OK;
+}
+
+int slimpipe_attn_merge(int32_t n_parts, const void* const* outs, const float* const* lses, int32_t part_dtype,
+                        int32_t batch, int32_t s_q, int32_t n_q_heads, int32_t head_dim, void* out,
+                        int32_t out_dtype, float* lse, void* hip_stream) {
+  if (!outs || !lses || !out || !lse) return SLIMPIPE_EINVAL_NULL;
+  if (n_parts < 1 || n_parts > 16) return SLIMPIPE_EINVAL_SHAPE;
+  if (batch <= 0 || s_q <= 0 || n_q_heads <= 0 || head_dim <= 0 || head_dim % 8 != 0) return SLIMPIPE_EINVAL_SHAPE;
+  if ((part_dtype != SLIMPIPE_BF16 && part_dtype != SLIMPIPE_F32) ||
+      (out_dtype != SLIMPIPE_BF16 && out_dtype != SLIMPIPE_F32))
+    return SLIMPIPE_EINVAL_SHAPE;
+  MergeArgs a;
+  memset(&a, 0, sizeof(a));
+  for (int i = 0; i < n_parts; ++i) {
+    if (!outs[i] || !lses[i]) return SLIMPIPE_EINVAL_NULL;
+    if (!aligned16(outs[i]) || (reinterpret_cast<uintptr_t>(lses[i]) & 3u)) return SLIMPIPE_EINVAL_ALIGN;
+    a.outs[i] = outs[i];
+    a.lses[i] = lses[i];
+  }
+  if (!aligned16(out) || (reinterpret_cast<uintptr_t>(lse) & 3u)) return SLIMPIPE_EINVAL_ALIGN;
+  a.n_parts = n_parts; a.part_f32 = (part_dtype == SLIMPIPE_F32); a.out_f32 = (out_dtype == SLIMPIPE_F32);
+  a.head_dim = head_dim; a.n_q_heads = n_q_heads; a.s_q = s_q; a.rows = (int64_t)batch * s_q;
+  a.out = out; a.lse = lse;
+  hipError_t e = launch_merge(a, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SLIMPIPE_OK : SLIMPIPE_ELAUNCH;
+}
+
+int slimpipe_attn_finalize_bf16(const float* acc, void* dst_bf16, int64_t n_elems, void* hip_stream) {
+  if (!acc || !dst_bf16) return SLIMPIPE_EINVAL_NULL;
+  if (n_elems < 0) return SLIMPIPE_EINVAL_SHAPE;
+  if (!aligned16(acc) || (reinterpret_cast<uintptr_t>(dst_bf16) & 7u)) return SLIMPIPE_EINVAL_ALIGN;
+  hipError_t e = launch_finalize(acc, static_cast<__bf16*>(dst_bf16), n_elems, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SLIMPIPE_OK : SLIMPIPE_ELAUNCH;
+}
+
+const char* slimpipe_attn_strerror(int code) {
+  switch (code) {
+    case SLIMPIPE_OK: return "ok";
+    case SLIMPIPE_EINVAL_NULL: return "a required pointer is NULL";
+    case SLIMPIPE_EINVAL_SHAPE: return "invalid shape, head_dim, scale, flag or dtype";
+    case SLIMPIPE_EINVAL_RANGE: return "invalid q_offset / kv range / kv_capacity";
+    case SLIMPIPE_EINVAL_STRIDE: return "strides must be positive multiples of 8 elements and cover head_dim";
+    case SLIMPIPE_EINVAL_ALIGN: return "pointer not 16-byte aligned";
+    case SLIMPIPE_EWORKSPACE: return "workspace missing or too small";
+    case SLIMPIPE_ELAUNCH: return "HIP launch failed";
+    default: return "unknown slimpipe status";
+  }
+}
+
+}  // extern "C"

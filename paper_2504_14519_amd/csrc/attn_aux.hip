@@ -1,0 +1,96 @@
+// HBM-bound helpers of the hot path: the online-softmax merge of partial (out, lse) pairs
+// (paper Sec. 4.2.2: a remotely computed partial output is folded into the local one; Sec. 5:
+// the softmax normaliser travels with it) and the final rounding of fp32 gradient accumulators.
+#include "kernels.hpp"
+#include "tile_common.hpp"
+
+namespace slimpipe {
+
+// One thread per 8 consecutive head_dim elements of one (row, head).
+//   lse = m + ln sum_r exp(lse_r - m),  out = sum_r exp(lse_r - lse) out_r ; parts with lse_r = -inf weigh 0.
+__global__ __launch_bounds__(256) void attn_merge_kernel(const MergeArgs a) {
+  const int nc = a.head_dim / 8;
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t total = a.rows * a.n_q_heads * nc;
+  if (gid >= total) return;
+  const int c = (int)(gid % nc);
+  const int64_t rh = gid / nc;                       // row * Hq + h
+  const int h = (int)(rh % a.n_q_heads);
+  const int64_t row = rh / a.n_q_heads;              // b * s_q + r
+  const int64_t bq = row / a.s_q, r = row % a.s_q;
+  const int64_t sidx = (bq * a.n_q_heads + h) * a.s_q + r;
+
+  float m = -INFINITY;
+  for (int p = 0; p < a.n_parts; ++p) m = fmaxf(m, a.lses[p][sidx]);
+  const bool has = m != -INFINITY;
+  float tot = 0.f;
+  if (has)
+    for (int p = 0; p < a.n_parts; ++p) tot += exp2_fast((a.lses[p][sidx] - m) * kLog2e);
+  const float lse = has ? m + __builtin_log2f(tot) * kLn2 : -INFINITY;
+  float acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+  const int64_t eoff = rh * a.head_dim + c * 8;
+  if (has) {
+    const float inv = 1.0f / tot;
+    for (int p = 0; p < a.n_parts; ++p) {
+      const float w = exp2_fast((a.lses[p][sidx] - m) * kLog2e) * inv;
+      if (a.part_f32) {
+        const f32x4* src = reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(a.outs[p]) + eoff);
+        const f32x4 x0 = src[0], x1 = src[1];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { acc[j] += w * x0[j]; acc[4 + j] += w * x1[j]; }
+      } else {
+        const bf16x8 x = *reinterpret_cast<const bf16x8*>(reinterpret_cast<const bf16_t*>(a.outs[p]) + eoff);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] += w * (float)x[j];
+      }
+    }
+  }
+  if (a.out_f32) {
+    f32x4* dst = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.out) + eoff);
+    dst[0] = f32x4{acc[0], acc[1], acc[2], acc[3]};
+    dst[1] = f32x4{acc[4], acc[5], acc[6], acc[7]};
+  } else {
+    bf16x8 o;
+#pragma unroll
+    for (int j = 0; j < 8; j += 2) {
+      bf16x2 h2 = __builtin_convertvector(f32x2{acc[j], acc[j + 1]}, bf16x2);
+      o[j] = h2[0];
+      o[j + 1] = h2[1];
+    }
+    *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16_t*>(a.out) + eoff) = o;
+  }
+  if (c == 0) a.lse[sidx] = lse;
+}
+
+hipError_t launch_merge(const MergeArgs& a, hipStream_t st) {
+  const int64_t total = a.rows * a.n_q_heads * (a.head_dim / 8);
+  if (total <= 0) return hipSuccess;
+  dim3 grid((unsigned)((total + 255) / 256)), block(256);
+  hipLaunchKernelGGL(attn_merge_kernel, grid, block, 0, st, a);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void finalize_bf16_kernel(const float* __restrict__ acc, bf16_t* __restrict__ dst, int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * 256 * 4;
+  for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4; i < n; i += stride) {
+    if (i + 4 <= n) {
+      const f32x4 v = *reinterpret_cast<const f32x4*>(acc + i);
+      *reinterpret_cast<bf16x4*>(dst + i) = __builtin_convertvector(v, bf16x4);
+    } else {
+      for (int64_t j = i; j < n; ++j) dst[j] = (bf16_t)acc[j];
+    }
+  }
+}
+
+hipError_t launch_finalize(const float* acc, __bf16* dst, int64_t n, hipStream_t st) {
+  if (n <= 0) return hipSuccess;
+  int64_t blocks = (n / 4 + 255) / 256;
+  if (blocks > 16384) blocks = 16384;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(finalize_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, st, acc, dst, n);
+  return hipGetLastError();
+}
+
+}  // namespace slimpipe

@@ -1,0 +1,59 @@
+// Host-visible argument blocks and launchers of the gfx950 kernels (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace slimpipe {
+
+struct FwdArgs {
+  const __bf16* q;
+  const __bf16* k;
+  const __bf16* v;
+  void* out;
+  float* lse;
+  int32_t s_q, n_q_heads, group, causal, out_f32;
+  int64_t q_offset, kv_begin, kv_end;
+  float scale_log2e;
+  int64_t q_stride_b, q_stride_s, q_stride_h;
+  int64_t kv_stride_b, kv_stride_s, kv_stride_h;
+  int64_t o_stride_b, o_stride_s, o_stride_h;
+};
+
+struct BwdArgs {
+  const __bf16* q;
+  const __bf16* k;
+  const __bf16* v;
+  const __bf16* out;
+  const __bf16* d_out;
+  const float* lse;
+  float* delta;            // workspace [batch, n_q_heads, s_q]
+  void* dq;
+  float* dk_acc;
+  float* dv_acc;
+  int32_t s_q, n_q_heads, n_kv_heads, group, causal;
+  int32_t dq_f32, dq_accumulate, dkv_accumulate;
+  int64_t q_offset, kv_begin, kv_end;
+  float scale, scale_log2e;
+  int64_t q_stride_b, q_stride_s, q_stride_h;
+  int64_t kv_stride_b, kv_stride_s, kv_stride_h;
+  int64_t o_stride_b, o_stride_s, o_stride_h;
+  int64_t do_stride_b, do_stride_s, do_stride_h;
+};
+
+struct MergeArgs {
+  const void* outs[16];
+  const float* lses[16];
+  int32_t n_parts, part_f32, out_f32, head_dim, n_q_heads, s_q;
+  int64_t rows;            // batch * s_q
+  void* out;
+  float* lse;
+};
+
+hipError_t launch_fwd(const FwdArgs& a, int batch, int head_dim, hipStream_t st);
+hipError_t launch_delta(const BwdArgs& a, int batch, int head_dim, hipStream_t st);
+hipError_t launch_bwd_dq(const BwdArgs& a, int batch, int head_dim, hipStream_t st);
+hipError_t launch_bwd_dkdv(const BwdArgs& a, int batch, int head_dim, hipStream_t st);
+hipError_t launch_merge(const MergeArgs& a, hipStream_t st);
+hipError_t launch_finalize(const float* acc, __bf16* dst, int64_t n, hipStream_t st);
+
+}  // namespace slimpipe

@@ -1,0 +1,137 @@
+// Device-side building blocks shared by the gfx950 attention kernels: bf16 MFMA operand types,
+// the swizzled LDS tile layout, cooperative global->LDS tile staging and the two LDS read
+// patterns (row-packed for contraction over head_dim, transposed for contraction over rows).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace slimpipe {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+#define SP_DEV __device__ __forceinline__
+
+// v_mfma_f32_32x32x16_bf16.  With lane = 32*g + r (r = lane & 31, g = lane >> 5):
+//   A (32 x 16): lane holds row r, k = 8g .. 8g+7
+//   B (16 x 32): lane holds column r, k = 8g .. 8g+7
+//   C (32 x 32): lane holds column r; register i is row 8*(i/4) + 4g + (i%4)
+// Because the contraction index is a dummy, the 8 k-slots of group g may stand for ANY 8 rows
+// of the contracted dimension as long as A and B agree; the kernels use that to feed a C-layout
+// tile straight back in as a B operand (slots of group g = rows 4g..4g+3 and 8+4g..8+4g+3 of a
+// 16-row step), with the matching A operand coming from the transposed LDS read below.
+SP_DEV f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+SP_DEV float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// max / sum over the two half-waves (lanes l and l^32 hold the same column of a C tile).
+SP_DEV float xhalf_max(float v) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+SP_DEV float xhalf_sum(float v) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Pack 8 consecutive C-tile registers (float) into one bf16x8 B operand (RNE).
+SP_DEV bf16x8 pack8(const f32x16& c, int base) {
+  bf16x8 r;
+#pragma unroll
+  for (int j = 0; j < 8; j += 2) {
+    f32x2 f = {c[base + j], c[base + j + 1]};
+    bf16x2 h = __builtin_convertvector(f, bf16x2);
+    r[j] = h[0];
+    r[j + 1] = h[1];
+  }
+  return r;
+}
+
+// ---------------------------------------------------------------------------------------------
+// LDS tile: ROWS x D bf16, row-major, rows of D*2 bytes split into 16-byte chunks whose position
+// inside the row is XOR-swizzled with the row index.  For D = 128 (16 chunks, one 256-byte bank
+// line per row) chunk c = 4u+i of row 4a+k sits at 4(u^k) + (i ^ (a&3)): both the row-packed read
+// (16 consecutive rows, same chunk) and the transposed read (4 consecutive rows x 4 consecutive
+// chunks) then touch 16 distinct 16-byte bank groups.  D = 64 uses c ^ (row & 7).
+template <int D>
+SP_DEV int tile_off(int row, int chunk) {
+  if constexpr (D == 128) {
+    const int u = chunk >> 2, i = chunk & 3;
+    const int p = (((u ^ row) & 3) << 2) | ((i ^ (row >> 2)) & 3);
+    return row * (D * 2) + (p << 4);
+  } else {
+    return row * (D * 2) + (((chunk ^ row) & (D / 8 - 1)) << 4);
+  }
+}
+
+// Row-packed operand: 8 consecutive head_dim elements [16*ks + 8g, +8) of tile row `row`.
+template <int D>
+SP_DEV bf16x8 lds_read_rowpacked(const char* tile, int row, int ks, int g) {
+  return *reinterpret_cast<const bf16x8*>(tile + tile_off<D>(row, 2 * ks + g));
+}
+
+// Transposed operand through ds_read_b64_tr_b16.  Within each block of 16 lanes the instruction
+// returns to lane i, element e, the (i%4)-th 16-bit element of the 8 bytes addressed by lane
+// 4e + i/4 of the block.  Pointing lane j of block b at row (row0 + 4*(b>>1) + j/4), columns
+// 32*db + 16*(b&1) + 4*(j%4) .. +3 therefore hands lane l the column 32*db + (l&31) of rows
+// row0 + 4g .. row0 + 4g+3; a second read 8 rows further completes the 8 k-slots of group g.
+template <int D>
+SP_DEV bf16x8 lds_read_transposed(const char* tile, int row0, int db, int lane) {
+  const int j = lane & 15, b = lane >> 4;
+  const int row = row0 + ((b >> 1) << 2) + (j >> 2);
+  const int chunk = 4 * db + 2 * (b & 1) + ((j & 3) >> 1);
+  const int sub = (j & 1) << 3;
+  typedef bf16x4 __attribute__((address_space(3))) * lds_v4_ptr;
+  bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4_ptr)(tile + tile_off<D>(row, chunk) + sub));
+  bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4_ptr)(tile + tile_off<D>(row + 8, chunk) + sub));
+  bf16x8 r;
+  r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
+  r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
+  return r;
+}
+
+// Cooperative staging of a ROWS x D bf16 tile: global -> registers (issue early) -> LDS (commit late).
+// Row r of the tile is global row min(row0 + r, row_last); callers mask what the clamp duplicates.
+template <int D, int ROWS, int THREADS>
+struct TileStage {
+  static constexpr int NC = D / 8;
+  static constexpr int CHUNKS = ROWS * NC;
+  static constexpr int PER_THREAD = (CHUNKS + THREADS - 1) / THREADS;
+  u32x4 regs[PER_THREAD];
+
+  SP_DEV void issue(const bf16_t* base, int64_t row_stride, int64_t row0, int64_t row_last, int tid) {
+#pragma unroll
+    for (int n = 0; n < PER_THREAD; ++n) {
+      const int id = tid + n * THREADS;
+      if (CHUNKS % THREADS == 0 || id < CHUNKS) {
+        const int r = id / NC, c = id % NC;
+        int64_t gr = row0 + r;
+        gr = gr < row_last ? gr : row_last;
+        regs[n] = *reinterpret_cast<const u32x4*>(base + gr * row_stride + c * 8);
+      }
+    }
+  }
+  SP_DEV void commit(char* tile, int tid) const {
+#pragma unroll
+    for (int n = 0; n < PER_THREAD; ++n) {
+      const int id = tid + n * THREADS;
+      if (CHUNKS % THREADS == 0 || id < CHUNKS) {
+        const int r = id / NC, c = id % NC;
+        *reinterpret_cast<u32x4*>(tile + tile_off<D>(r, c)) = regs[n];
+      }
+    }
+  }
+};
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+}  // namespace slimpipe

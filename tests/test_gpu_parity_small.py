@@ -1,0 +1,199 @@
+"""HIP path vs fp64 oracle, element by element, at sizes the oracle finishes in seconds.
+Everything goes through the C ABI (via the ctypes binding)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import attn_fwd, attn_bwd, attn_merge
+from synth_inputs import CONFIGS, normal_bf16, bf16_bits_to_f64
+from gpu_util import say, dev_bf16, host_f64, rel_l2, max_abs, TOL_OUT, TOL_LSE, TOL_GRAD
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sp():
+    import torch
+    assert torch.cuda.is_available(), "needs the MI355X"
+    import paper_2504_14519_amd as sp_
+    return sp_
+
+
+def check_fwd(name, o_gpu, lse_gpu, o_ref, lse_ref, bf16_out=True):
+    eo = max_abs(host_f64(o_gpu), o_ref)
+    el = max_abs(host_f64(lse_gpu), lse_ref)
+    assert np.array_equal(np.isneginf(host_f64(lse_gpu)), np.isneginf(lse_ref)), name + ": -inf pattern of lse differs"
+    say("%s: out max-abs %.3e  lse max-abs %.3e" % (name, eo, el))
+    if bf16_out:
+        # a bf16 result cannot be closer than half an ulp: the 1e-2 bound holds for |out| < 4
+        assert np.abs(o_ref).max() < 4.0
+    assert eo <= TOL_OUT, name
+    assert el <= TOL_LSE, name
+
+
+def check_grad(name, g_gpu, g_ref):
+    e = rel_l2(host_f64(g_gpu), g_ref)
+    say("%s: rel-L2 %.3e" % (name, e))
+    assert e <= TOL_GRAD, name
+
+
+def run_sliced(sp, cfg_id, B, N, n, Hq, Hkv, D, splits=()):
+    import torch
+    s = N // n
+    scale = 1.0 / math.sqrt(D)
+    qb, kb, vb, dob = (normal_bf16((B, N, H, D), cfg_id, t) for t, H in (("q", Hq), ("k", Hkv), ("v", Hkv), ("do", Hq)))
+    q64, k64, v64, do64 = (bf16_bits_to_f64(x) for x in (qb, kb, vb, dob))
+    q, k, v, do = (dev_bf16(x) for x in (qb, kb, vb, dob))
+    dk_acc = torch.zeros((B, N, Hkv, D), device="cuda:0", dtype=torch.float32)
+    dv_acc = torch.zeros_like(dk_acc)
+    outs, lses = {}, {}
+    for i in range(n):
+        say("cfg%d fwd slice %d" % (cfg_id, i))
+        o, l = sp.slimpipe_attn_fwd(q[:, i * s:(i + 1) * s], k, v, i * s, 0, (i + 1) * s, True, scale)
+        torch.cuda.synchronize()
+        o_ref, l_ref = attn_fwd(q64[:, i * s:(i + 1) * s], k64, v64, i * s, 0, (i + 1) * s, True, scale)
+        check_fwd("cfg%d fwd slice %d" % (cfg_id, i), o, l, o_ref, l_ref)
+        outs[i], lses[i] = (o, l), (o_ref, l_ref)
+    dk_ref = np.zeros((B, N, Hkv, D))
+    dv_ref = np.zeros((B, N, Hkv, D))
+    for i in reversed(range(n)):
+        say("cfg%d bwd slice %d" % (cfg_id, i))
+        sl = slice(i * s, (i + 1) * s)
+        o, l = outs[i]
+        dq = sp.slimpipe_attn_bwd(q[:, sl], k, v, o, do[:, sl], l, i * s, 0, (i + 1) * s, dk_acc, dv_acc, True, scale,
+                                  dq_dtype=sp.F32, dkv_accumulate=True)
+        torch.cuda.synchronize()
+        # the oracle gets exactly what the kernel got: the bf16 out and fp32 lse of the forward
+        dq_r, dk_r, dv_r = attn_bwd(q64[:, sl], k64, v64, host_f64(o), do64[:, sl], host_f64(l), i * s, 0, (i + 1) * s, True, scale)
+        check_grad("cfg%d dq slice %d" % (cfg_id, i), dq, dq_r)
+        dk_ref += dk_r
+        dv_ref += dv_r
+    check_grad("cfg%d dk (all slices)" % cfg_id, dk_acc, dk_ref)
+    check_grad("cfg%d dv (all slices)" % cfg_id, dv_acc, dv_ref)
+    dk_b = sp.slimpipe_attn_finalize_bf16(dk_acc)
+    check_grad("cfg%d dk finalized bf16" % cfg_id, dk_b, dk_ref)
+
+    i = n - 1
+    sl = slice(i * s, (i + 1) * s)
+    for cuts in splits:
+        say("cfg%d split of last slice at %s" % (cfg_id, cuts))
+        edges = [0] + list(cuts) + [N]
+        parts = [sp.slimpipe_attn_fwd(q[:, sl], k, v, i * s, a, b, True, scale, out_dtype=sp.F32) for a, b in zip(edges[:-1], edges[1:])]
+        om, lm = sp.slimpipe_attn_merge([p[0] for p in parts], [p[1] for p in parts])
+        torch.cuda.synchronize()
+        for (po, pl), a, b in zip(parts, edges[:-1], edges[1:]):
+            r_o, r_l = attn_fwd(q64[:, sl], k64, v64, i * s, a, b, True, scale)
+            check_fwd("  part [%d,%d)" % (a, b), po, pl, r_o, r_l, bf16_out=False)
+        check_fwd("  merged", om, lm, lses[i][0], lses[i][1])
+        # oracle merge of the oracle parts equals the unsplit oracle result (identity of the method)
+        # backward per part with the merged (out, lse); dq summed, dk/dv placed per range
+        dk2 = torch.zeros_like(dk_acc)
+        dv2 = torch.zeros_like(dk_acc)
+        dq2 = torch.zeros((B, s, Hq, D), device="cuda:0", dtype=torch.float32)
+        for a, b in zip(edges[:-1], edges[1:]):
+            sp.slimpipe_attn_bwd(q[:, sl], k, v, om, do[:, sl], lm, i * s, a, b, dk2, dv2, True, scale,
+                                 dq=dq2, dq_dtype=sp.F32, dq_accumulate=True, dkv_accumulate=False)
+        torch.cuda.synchronize()
+        dq_r, dk_r, dv_r = attn_bwd(q64[:, sl], k64, v64, host_f64(om), do64[:, sl], host_f64(lm), i * s, 0, N, True, scale)
+        check_grad("  split dq", dq2, dq_r)
+        check_grad("  split dk", dk2, dk_r)
+        check_grad("  split dv", dv2, dv_r)
+
+
+def test_config_tiny_full(sp):
+    c = CONFIGS[0]
+    run_sliced(sp, 0, 1, c["N"], c["n"], c["Hq"], c["Hkv"], c["D"], splits=[(1024,), (1500,), (1800,), (512, 1537, 2000)])
+
+
+def test_d128_gqa_sliced_full(sp):
+    run_sliced(sp, 5, 1, 1536, 3, 8, 2, 128, splits=[(700,), (1100, 1300)])
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_ragged_unaligned_strided(sp, D):
+    """s_q, the range ends and q_offset are not multiples of any tile; batch 2; GQA; q/k/v are views
+    with padded strides; covers range starting inside / ending inside the diagonal block."""
+    import torch
+    B, s, Hq, Hkv, Nkv = 2, 200, 4, 2, 777
+    scale = 0.11
+    qb = normal_bf16((B, s, Hq, D + 8), 6, "q", salt=D)
+    kb = normal_bf16((B, Nkv, Hkv + 1, D), 6, "k", salt=D)
+    vb = normal_bf16((B, Nkv, Hkv + 1, D), 6, "v", salt=D)
+    dob = normal_bf16((B, s, Hq, D), 6, "do", salt=D)
+    q = dev_bf16(qb)[..., :D]
+    k = dev_bf16(kb)[:, :, :Hkv]
+    v = dev_bf16(vb)[:, :, :Hkv]
+    do = dev_bf16(dob)
+    q64, k64, v64, do64 = bf16_bits_to_f64(qb)[..., :D], bf16_bits_to_f64(kb)[:, :, :Hkv], bf16_bits_to_f64(vb)[:, :, :Hkv], bf16_bits_to_f64(dob)
+    cases = [(500, 13, 650, True), (500, 0, 777, True), (500, 601, 777, True), (0, 0, 200, True), (3, 1, 777, False),
+             (500, 700, 777, True), (100, 290, 310, True)]
+    for (q_off, a, b, causal) in cases:
+        name = "ragged D%d q_off %d range [%d,%d) causal %d" % (D, q_off, a, b, causal)
+        say(name)
+        o, l = sp.slimpipe_attn_fwd(q, k, v, q_off, a, b, causal, scale, out_dtype=sp.F32)
+        torch.cuda.synchronize()
+        o_ref, l_ref = attn_fwd(q64, k64, v64, q_off, a, b, causal, scale)
+        check_fwd(name, o, l, o_ref, l_ref, bf16_out=False)
+        ob = o.to(torch.bfloat16)
+        dk_acc = torch.full((B, Nkv, Hkv + 1, D), 7.0, device="cuda:0", dtype=torch.float32)[:, :, :Hkv]
+        dv_acc = torch.full((B, Nkv, Hkv + 1, D), 7.0, device="cuda:0", dtype=torch.float32)[:, :, :Hkv]
+        dq = torch.empty((B, s, Hq, D + 8), device="cuda:0", dtype=torch.bfloat16)[..., :D]
+        sp.slimpipe_attn_bwd(q, k, v, ob, do, l, q_off, a, b, dk_acc, dv_acc, causal, scale, dq=dq, dq_dtype=sp.BF16,
+                             dkv_accumulate=False)
+        torch.cuda.synchronize()
+        dq_r, dk_r, dv_r = attn_bwd(q64, k64, v64, host_f64(ob), do64, host_f64(l), q_off, a, b, causal, scale)
+        if np.linalg.norm(dq_r) > 0:
+            check_grad(name + " dq", dq, dq_r)
+            check_grad(name + " dk", dk_acc[:, a:b], dk_r[:, a:b])
+            check_grad(name + " dv", dv_acc[:, a:b], dv_r[:, a:b])
+        else:
+            assert float(dq.float().abs().max()) == 0.0
+        # rows outside the range are untouched
+        hk = host_f64(dk_acc)
+        assert np.all(hk[:, :a] == 7.0) and np.all(hk[:, b:] == 7.0), name
+        hv = host_f64(dv_acc)
+        assert np.all(hv[:, :a] == 7.0) and np.all(hv[:, b:] == 7.0), name
+
+
+def test_empty_range_and_rows_without_keys(sp):
+    import torch
+    B, s, Hq, Hkv, D, Nkv = 1, 96, 2, 1, 128, 256
+    qb, kb, vb, dob = normal_bf16((B, s, Hq, D), 7, "q"), normal_bf16((B, Nkv, Hkv, D), 7, "k"), normal_bf16((B, Nkv, Hkv, D), 7, "v"), normal_bf16((B, s, Hq, D), 7, "do")
+    q, k, v, do = dev_bf16(qb), dev_bf16(kb), dev_bf16(vb), dev_bf16(dob)
+    for (q_off, a, b) in [(100, 50, 50), (100, 230, 256), (100, 150, 256)]:
+        say("empty/partly empty: q_off %d range [%d,%d)" % (q_off, a, b))
+        o, l = sp.slimpipe_attn_fwd(q, k, v, q_off, a, b, True, 0.09, out_dtype=sp.F32)
+        torch.cuda.synchronize()
+        o_ref, l_ref = attn_fwd(bf16_bits_to_f64(qb), bf16_bits_to_f64(kb), bf16_bits_to_f64(vb), q_off, a, b, True, 0.09)
+        check_fwd("empty case", o, l, o_ref, l_ref, bf16_out=False)
+        assert not np.isnan(host_f64(o)).any()
+        dk_acc = torch.zeros((B, Nkv, Hkv, D), device="cuda:0")
+        dv_acc = torch.zeros_like(dk_acc)
+        dq = sp.slimpipe_attn_bwd(q, k, v, o.to(torch.bfloat16), do, l, q_off, a, b, dk_acc, dv_acc, True, 0.09, dq_dtype=sp.F32)
+        torch.cuda.synchronize()
+        for t in (dq, dk_acc, dv_acc):
+            assert not torch.isnan(t).any()
+        dq_r, dk_r, dv_r = attn_bwd(bf16_bits_to_f64(qb), bf16_bits_to_f64(kb), bf16_bits_to_f64(vb), host_f64(o.to(torch.bfloat16)),
+                                    bf16_bits_to_f64(dob), host_f64(l), q_off, a, b, True, 0.09)
+        assert max_abs(host_f64(dq), dq_r) < 1e-2 * max(1.0, np.abs(dq_r).max())
+        rows_empty = np.isneginf(l_ref[0, 0])
+        assert np.all(host_f64(dq)[0, rows_empty] == 0)
+
+
+def test_dkdv_bit_reproducible(sp):
+    import torch
+    B, s, Hq, Hkv, D, Nkv = 1, 512, 8, 1, 128, 1024
+    qb, kb, vb, dob = normal_bf16((B, s, Hq, D), 8, "q"), normal_bf16((B, Nkv, Hkv, D), 8, "k"), normal_bf16((B, Nkv, Hkv, D), 8, "v"), normal_bf16((B, s, Hq, D), 8, "do")
+    q, k, v, do = dev_bf16(qb), dev_bf16(kb), dev_bf16(vb), dev_bf16(dob)
+    o, l = sp.slimpipe_attn_fwd(q, k, v, 512, 0, 1024, True, None)
+    res = []
+    for rep in range(3):
+        say("determinism run %d" % rep)
+        dk_acc = torch.zeros((B, Nkv, Hkv, D), device="cuda:0")
+        dv_acc = torch.zeros_like(dk_acc)
+        dq = sp.slimpipe_attn_bwd(q, k, v, o, do, l, 512, 0, 1024, dk_acc, dv_acc, True, None, dq_dtype=sp.F32)
+        torch.cuda.synchronize()
+        res.append((dk_acc.cpu(), dv_acc.cpu(), dq.cpu()))
+    for r in res[1:]:
+        assert torch.equal(r[0], res[0][0]) and torch.equal(r[1], res[0][1]) and torch.equal(r[2], res[0][2])
