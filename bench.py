@@ -1,0 +1,190 @@
+#!/usr/bin/env python3
+"""Benchmark of the sliced causal attention hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one synthetic microbatch: forward of every slice
+in order against its cached K/V prefix, then backward of every slice in reverse order with dK/dV
+accumulated in fp32 (the call order of the slice-wise schedule, paper Sec. 4.1.2).  Inputs are
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama70b_tp8_share] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+
+
+def visible_pairs(s, q_offset, kv_begin, kv_end):
+    """Visible (query row, key) pairs of one causal call, per query head."""
+    total = 0
+    full_rows_from = max(0, kv_end - 1 - q_offset)          # rows r >= this see the whole range
+    full_rows_from = min(full_rows_from, s)
+    # rows r < full_rows_from see keys kv_begin .. q_offset + r
+    lo_r = max(0, kv_begin - q_offset)                      # first row that sees anything
+    if lo_r < full_rows_from:
+        n = full_rows_from - lo_r
+        first = q_offset + lo_r + 1 - kv_begin
+        total += n * first + n * (n - 1) // 2
+    total += (s - full_rows_from) * max(0, kv_end - kv_begin)
+    return total
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="llama70b_tp8_share")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2504_14519_amd as sp
+    from synth_inputs import CONFIGS, normal_bf16
+
+    cfg_id = [i for i, c in CONFIGS.items() if c["name"] == args.workload]
+    if not cfg_id:
+        sys.exit("unknown workload %s" % args.workload)
+    cfg_id = cfg_id[0]
+    c = CONFIGS[cfg_id]
+    N, n, Hq, Hkv, D = c["N"], c["n"], c["Hq"], c["Hkv"], c["D"]
+    s = N // n
+    first_slice = n - 8 if c["name"] == "longest" else 0     # the longest config runs its final 8 slices only
+    scale = 1.0 / math.sqrt(D)
+    dev = "cuda:0"
+
+    def to_dev(bits):
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(dev)
+
+    q = to_dev(normal_bf16((1, N, Hq, D), cfg_id, "q")) if first_slice == 0 else None
+    if q is None:   # only the slices that run need queries
+        qn = normal_bf16((1, (n - first_slice) * s, Hq, D), cfg_id, "q")
+        don = normal_bf16((1, (n - first_slice) * s, Hq, D), cfg_id, "do")
+        q, do = to_dev(qn), to_dev(don)
+    else:
+        do = to_dev(normal_bf16((1, N, Hq, D), cfg_id, "do"))
+    k = to_dev(normal_bf16((1, N, Hkv, D), cfg_id, "k"))
+    v = to_dev(normal_bf16((1, N, Hkv, D), cfg_id, "v"))
+    slices = list(range(first_slice, n))
+    nrun = len(slices)
+    outs = [torch.empty((1, s, Hq, D), device=dev, dtype=torch.bfloat16) for _ in slices]
+    lses = [torch.empty((1, Hq, s), device=dev, dtype=torch.float32) for _ in slices]
+    dq = torch.empty((1, nrun * s, Hq, D), device=dev, dtype=torch.bfloat16)
+    dk_acc = torch.zeros((1, N, Hkv, D), device=dev, dtype=torch.float32)
+    dv_acc = torch.zeros((1, N, Hkv, D), device=dev, dtype=torch.float32)
+    dk_out = torch.empty((1, N, Hkv, D), device=dev, dtype=torch.bfloat16)
+    dv_out = torch.empty((1, N, Hkv, D), device=dev, dtype=torch.bfloat16)
+    ws = torch.empty(Hq * s * 4 + 256, device=dev, dtype=torch.uint8)
+
+    def qs(j):
+        return slice(j * s, (j + 1) * s)
+
+    def step():
+        for j, i in enumerate(slices):
+            sp.slimpipe_attn_fwd(q[:, qs(j)], k, v, i * s, 0, (i + 1) * s, True, scale, out=outs[j], lse=lses[j])
+        for j in reversed(range(nrun)):
+            i = slices[j]
+            # the last slice to run backward first overwrites its dK/dV rows; earlier slices add to them
+            sp.slimpipe_attn_bwd(q[:, qs(j)], k, v, outs[j], do[:, qs(j)], lses[j], i * s, 0, (i + 1) * s, dk_acc, dv_acc,
+                                 True, scale, dq=dq[:, qs(j)], dq_dtype=sp.BF16, dkv_accumulate=(j != nrun - 1), workspace=ws)
+        sp.slimpipe_attn_finalize_bf16(dk_acc, dk_out)
+        sp.slimpipe_attn_finalize_bf16(dv_acc, dv_out)
+
+    pairs = [visible_pairs(s, i * s, 0, (i + 1) * s) for i in slices]
+    pairs_total = sum(pairs)
+    flops_step = 14.0 * D * Hq * pairs_total            # fwd 4D + bwd 10D per visible pair per q head
+    flops_step_model = 12.0 * D * Hq * pairs_total
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    sp.slimpipe_attn_profile_enable(True)
+    sp.slimpipe_attn_profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = sp.slimpipe_attn_profile_read()
+    sp.slimpipe_attn_profile_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    # dominant kernel = the one with the largest share of the timed region
+    alg_flops = {"fwd": 4.0, "dq": 6.0, "dkdv": 8.0}       # x D x Hq x pairs: what each kernel computes
+    kshare = {kk: prof[kk][0] for kk in alg_flops}
+    dom = max(kshare, key=kshare.get)
+    dom_ms, dom_n = prof[dom]
+    dom_flops_total = alg_flops[dom] * D * Hq * pairs_total * args.steps
+    achieved = dom_flops_total / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
+    roofline = {
+        "bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+        "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+        "launches": int(dom_n), "avg_launch_ms": round(dom_ms / max(1, dom_n), 4),
+        "flops_per_launch_avg": dom_flops_total / max(1, dom_n),
+        "kernel_ms_per_step": {kk: round(prof[kk][0] / args.steps, 3) for kk in prof},
+        "kernel_tflops": {kk: round(alg_flops[kk] * D * Hq * pairs_total * args.steps / (prof[kk][0] * 1e-3) / 1e12, 1)
+                          for kk in alg_flops if prof[kk][0] > 0},
+    }
+
+    out = {
+        "metric": "sliced causal attn fwd+bwd TFLOP/s and % of MI355X bf16 MFMA peak",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": c["name"], "seq": N, "slices": n, "slice_len": s, "slices_run": [slices[0], slices[-1]],
+                   "q_heads": Hq, "kv_heads": Hkv, "head_dim": D, "flop_convention": "14*D per visible pair per q head"},
+        "pct_of_bf16_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
+        "value_model_flops_12D": round(flops_step_model / (ms_per_step * 1e-3) / 1e12, 2),
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg_id, c, s, scale)
+    print(json.dumps(out), flush=True)
+
+
+def cpu_baseline(cfg_id, c, s, scale):
+    """The fp64 oracle, as it stands, timed on the host cores on a bounded sample of the workload."""
+    import numpy as np
+    from oracle import attn_fwd, attn_bwd
+    from synth_inputs import normal_bf16, bf16_bits_to_f64
+    Hq, Hkv, D = c["Hq"], c["Hkv"], c["D"]
+    rows = min(s, 1024)
+    i = min(2, c["n"] - 1)                        # third slice: two cached slices + the diagonal block
+    kv_end = i * s + rows
+    rng_cfg = 15                                  # its own seed family: a sample, not the workload tensors
+    q = bf16_bits_to_f64(normal_bf16((1, rows, Hq, D), rng_cfg, "q"))
+    do = bf16_bits_to_f64(normal_bf16((1, rows, Hq, D), rng_cfg, "do"))
+    k = bf16_bits_to_f64(normal_bf16((1, kv_end, Hkv, D), rng_cfg, "k"))
+    v = bf16_bits_to_f64(normal_bf16((1, kv_end, Hkv, D), rng_cfg, "v"))
+    t0 = time.perf_counter()
+    o, lse = attn_fwd(q, k, v, i * s, 0, kv_end, True, scale)
+    attn_bwd(q, k, v, o, do, lse, i * s, 0, kv_end, True, scale)
+    dt = time.perf_counter() - t0
+    pairs = visible_pairs(rows, i * s, 0, kv_end)
+    tf = 14.0 * D * Hq * pairs / dt / 1e12
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count()
+    return {"value": round(tf, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": "fwd+bwd of the first %d rows of slice %d (all %d q heads) against keys [0,%d), fp64 numpy; %.1f s"
+                      % (rows, i, Hq, kv_end, dt)}
+
+
+if __name__ == "__main__":
+    main()

@@ -11,7 +11,7 @@
  *
  * Conventions
  *   - All data pointers are DEVICE pointers owned by the caller.  The library allocates nothing on
- *     the device, keeps no state between calls, enqueues its kernels on the caller's HIP stream
+ *     the device, keeps no state between calls (but for the optional profiling switch below), enqueues its kernels on the caller's HIP stream
  *     (a hipStream_t passed as void*, NULL = default stream) and returns without synchronising.
  *   - q, out, d_out, dq:  [batch, s_q, n_q_heads, head_dim], element strides given, head_dim contiguous.
  *   - k, v, dk_acc, dv_acc: [batch, kv_capacity, n_kv_heads, head_dim]; row j of the prefix IS global
@@ -119,6 +119,17 @@ int slimpipe_attn_merge(int32_t n_parts, const void* const* outs, const float* c
 int slimpipe_attn_finalize_bf16(const float* acc, void* dst_bf16, int64_t n_elems, void* hip_stream);
 
 const char* slimpipe_attn_strerror(int code);
+
+/* Optional per-kernel timing for benchmarks (not part of the paper's method).  While enabled, every
+ * kernel the library enqueues is bracketed by HIP events recorded on the caller's stream.
+ * slimpipe_attn_profile_read waits for the recorded events, adds up the elapsed time per kernel kind
+ * since the last read and clears the records.  The only state the library keeps; not thread-safe. */
+enum {
+  SLIMPIPE_KERNEL_FWD = 0, SLIMPIPE_KERNEL_DELTA = 1, SLIMPIPE_KERNEL_DQ = 2, SLIMPIPE_KERNEL_DKDV = 3,
+  SLIMPIPE_KERNEL_MERGE = 4, SLIMPIPE_KERNEL_FINALIZE = 5, SLIMPIPE_KERNEL_KINDS = 6
+};
+int slimpipe_attn_profile_enable(int enable);
+int slimpipe_attn_profile_read(double total_ms[SLIMPIPE_KERNEL_KINDS], int64_t launches[SLIMPIPE_KERNEL_KINDS]);
 
 #ifdef __cplusplus
 }

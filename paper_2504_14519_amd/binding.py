@@ -54,6 +54,10 @@ def _load():
     L.slimpipe_attn_merge.restype = ctypes.c_int
     L.slimpipe_attn_finalize_bf16.argtypes = [vp, vp, i64, vp]
     L.slimpipe_attn_finalize_bf16.restype = ctypes.c_int
+    L.slimpipe_attn_profile_enable.argtypes = [ctypes.c_int]
+    L.slimpipe_attn_profile_enable.restype = ctypes.c_int
+    L.slimpipe_attn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    L.slimpipe_attn_profile_read.restype = ctypes.c_int
     L.slimpipe_attn_strerror.argtypes = [ctypes.c_int]
     L.slimpipe_attn_strerror.restype = ctypes.c_char_p
     return L
@@ -169,3 +173,18 @@ def slimpipe_attn_finalize_bf16(acc, dst=None):
         dst = torch.empty(acc.shape, device=acc.device, dtype=torch.bfloat16)
     _check(lib.slimpipe_attn_finalize_bf16(acc.data_ptr(), dst.data_ptr(), acc.numel(), _stream()), "finalize_bf16")
     return dst
+
+
+KERNEL_KINDS = ("fwd", "delta", "dq", "dkdv", "merge", "finalize")
+
+
+def slimpipe_attn_profile_enable(enable):
+    _check(lib.slimpipe_attn_profile_enable(1 if enable else 0), "profile_enable")
+
+
+def slimpipe_attn_profile_read():
+    """-> {kernel kind: (total ms, launches)} since the last read (waits for the recorded events)."""
+    ms = (ctypes.c_double * len(KERNEL_KINDS))()
+    n = (ctypes.c_int64 * len(KERNEL_KINDS))()
+    _check(lib.slimpipe_attn_profile_read(ms, n), "profile_read")
+    return {k: (ms[i], n[i]) for i, k in enumerate(KERNEL_KINDS)}

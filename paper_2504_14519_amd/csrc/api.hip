@@ -2,6 +2,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <vector>
+
 #include "../../include/slimpipe_attn.h"
 #include "kernels.hpp"
 
@@ -17,9 +19,56 @@ size_t delta_bytes(const slimpipe_attn_params* p) {
   return (n + 255) & ~(size_t)255;
 }
 
+
+// ---- optional per-kernel event timing -------------------------------------------------------
+struct ProfRecord { int kind; hipEvent_t start, stop; };
+bool g_prof_on = false;
+std::vector<ProfRecord> g_prof_records;
+std::vector<hipEvent_t> g_prof_free;
+
+hipEvent_t prof_event() {
+  if (!g_prof_free.empty()) { hipEvent_t e = g_prof_free.back(); g_prof_free.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+template <class F>
+hipError_t timed(int kind, hipStream_t st, F&& launch) {
+  if (!g_prof_on) return launch();
+  ProfRecord r{kind, prof_event(), prof_event()};
+  if (!r.start || !r.stop) return launch();
+  (void)hipEventRecord(r.start, st);
+  hipError_t e = launch();
+  (void)hipEventRecord(r.stop, st);
+  g_prof_records.push_back(r);
+  return e;
+}
+
 }  // namespace
 
 extern "C" {
+
+int slimpipe_attn_profile_enable(int enable) {
+  g_prof_on = enable != 0;
+  return SLIMPIPE_OK;
+}
+
+int slimpipe_attn_profile_read(double total_ms[SLIMPIPE_KERNEL_KINDS], int64_t launches[SLIMPIPE_KERNEL_KINDS]) {
+  if (!total_ms || !launches) return SLIMPIPE_EINVAL_NULL;
+  for (int i = 0; i < SLIMPIPE_KERNEL_KINDS; ++i) { total_ms[i] = 0.0; launches[i] = 0; }
+  int rc = SLIMPIPE_OK;
+  for (const ProfRecord& r : g_prof_records) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess)
+      rc = SLIMPIPE_ELAUNCH;
+    else if (r.kind >= 0 && r.kind < SLIMPIPE_KERNEL_KINDS) { total_ms[r.kind] += ms; launches[r.kind] += 1; }
+    g_prof_free.push_back(r.start);
+    g_prof_free.push_back(r.stop);
+  }
+  g_prof_records.clear();
+  return rc;
+}
 
 int slimpipe_attn_validate(const slimpipe_attn_params* p, int is_bwd) {
   if (!p) return SLIMPIPE_EINVAL_NULL;
@@ -77,7 +126,8 @@ int slimpipe_attn_fwd(const slimpipe_attn_params* p, const void* q_slice, const 
   a.q_stride_b = p->q_stride_b; a.q_stride_s = p->q_stride_s; a.q_stride_h = p->q_stride_h;
   a.kv_stride_b = p->kv_stride_b; a.kv_stride_s = p->kv_stride_s; a.kv_stride_h = p->kv_stride_h;
   a.o_stride_b = p->o_stride_b; a.o_stride_s = p->o_stride_s; a.o_stride_h = p->o_stride_h;
-  hipError_t e = launch_fwd(a, p->batch, p->head_dim, static_cast<hipStream_t>(hip_stream));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = timed(SLIMPIPE_KERNEL_FWD, st, [&] { return launch_fwd(a, p->batch, p->head_dim, st); });
   return e == hipSuccess ? SLIMPIPE_OK : SLIMPIPE_ELAUNCH;
 }
 
@@ -117,9 +167,9 @@ int slimpipe_attn_bwd(const slimpipe_attn_params* p, const void* q_slice, const 
   a.o_stride_b = p->o_stride_b; a.o_stride_s = p->o_stride_s; a.o_stride_h = p->o_stride_h;
   a.do_stride_b = p->do_stride_b; a.do_stride_s = p->do_stride_s; a.do_stride_h = p->do_stride_h;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  if (launch_delta(a, p->batch, p->head_dim, st) != hipSuccess) return SLIMPIPE_ELAUNCH;
-  if (launch_bwd_dq(a, p->batch, p->head_dim, st) != hipSuccess) return SLIMPIPE_ELAUNCH;
-  if (launch_bwd_dkdv(a, p->batch, p->head_dim, st) != hipSuccess) return SLIMPIPE_ELAUNCH;
+  if (timed(SLIMPIPE_KERNEL_DELTA, st, [&] { return launch_delta(a, p->batch, p->head_dim, st); }) != hipSuccess) return SLIMPIPE_ELAUNCH;
+  if (timed(SLIMPIPE_KERNEL_DQ, st, [&] { return launch_bwd_dq(a, p->batch, p->head_dim, st); }) != hipSuccess) return SLIMPIPE_ELAUNCH;
+  if (timed(SLIMPIPE_KERNEL_DKDV, st, [&] { return launch_bwd_dkdv(a, p->batch, p->head_dim, st); }) != hipSuccess) return SLIMPIPE_ELAUNCH;
   return SLIMPIPE_OK;
 }
 
@@ -144,7 +194,8 @@ int slimpipe_attn_merge(int32_t n_parts, const void* const* outs, const float* c
   a.n_parts = n_parts; a.part_f32 = (part_dtype == SLIMPIPE_F32); a.out_f32 = (out_dtype == SLIMPIPE_F32);
   a.head_dim = head_dim; a.n_q_heads = n_q_heads; a.s_q = s_q; a.rows = (int64_t)batch * s_q;
   a.out = out; a.lse = lse;
-  hipError_t e = launch_merge(a, static_cast<hipStream_t>(hip_stream));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = timed(SLIMPIPE_KERNEL_MERGE, st, [&] { return launch_merge(a, st); });
   return e == hipSuccess ? SLIMPIPE_OK : SLIMPIPE_ELAUNCH;
 }
 
@@ -152,7 +203,8 @@ int slimpipe_attn_finalize_bf16(const float* acc, void* dst_bf16, int64_t n_elem
   if (!acc || !dst_bf16) return SLIMPIPE_EINVAL_NULL;
   if (n_elems < 0) return SLIMPIPE_EINVAL_SHAPE;
   if (!aligned16(acc) || (reinterpret_cast<uintptr_t>(dst_bf16) & 7u)) return SLIMPIPE_EINVAL_ALIGN;
-  hipError_t e = launch_finalize(acc, static_cast<__bf16*>(dst_bf16), n_elems, static_cast<hipStream_t>(hip_stream));
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = timed(SLIMPIPE_KERNEL_FINALIZE, st, [&] { return launch_finalize(acc, static_cast<__bf16*>(dst_bf16), n_elems, st); });
   return e == hipSuccess ? SLIMPIPE_OK : SLIMPIPE_ELAUNCH;
 }
 
