@@ -13,6 +13,8 @@
 //     group in a fixed order: S = Q K^T, dP = dO V^T land with one key per lane and 16 query rows
 //     in the registers, which is the B operand of dV^T += dO^T P and dK^T += Q^T dS.
 //     One workgroup owns a key row outright, so dK/dV are bit-reproducible.
+#include <stdlib.h>
+
 #include "kernels.hpp"
 #include "tile_common.hpp"
 
@@ -141,16 +143,24 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
         }
       }
       const bool need_mask = (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
+      if (need_mask) {
+        int64_t kmax = a.kv_end - 1;
+        if (a.causal && qpos < kmax) kmax = qpos;
+        kmax -= key0;
+        const int kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int key_rel = kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+            s[kb][i] = key_rel <= kmax_rel ? s[kb][i] : -INFINITY;     // exp2(-inf) = 0
+          }
+      }
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          float p = exp2_fast(__builtin_fmaf(s[kb][i], c, -lse2));
-          if (need_mask) {
-            const int64_t key = key0 + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-            const bool vis = key < a.kv_end && (!a.causal || key <= qpos);
-            p = vis ? p : 0.f;
-          }
+          const float p = exp2_fast(__builtin_fmaf(s[kb][i], c, -lse2));
           s[kb][i] = p * (dp[kb][i] - delta);        // dS^T
         }
 #pragma unroll
@@ -214,13 +224,112 @@ hipError_t launch_bwd_dq(const BwdArgs& a, int batch, int head_dim, hipStream_t 
 }
 
 // ------------------------------------------------------------------------------------ dk / dv
+// LDS map of the dk/dv kernel: two 2*TILE-byte buffers (Q tile, dO tile), each buffer a power of
+// two in size so that switching buffers is one XOR on the lane offsets; row statistics behind them.
+
+// One 32-row query block against the wave's 32 keys: S = Q K^T and dP = dO V^T (row-packed A
+// operands from LDS, K/V B operands from registers).  `blk_off` = qb*32 rows in bytes.
+template <int D, int TILE_BYTES>
+SP_DEV void dkdv_scores(const char* smem, const LaneOffsets<D>& lo, int blk_off,
+                        const bf16x8 (&kreg)[D / 16], const bf16x8 (&vreg)[D / 16], f32x16& s, f32x16& dp) {
+  bf16x8 qa[D / 16], da[D / 16];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    qa[ks] = lds_rp<D>(smem, lo, ks, blk_off);
+    da[ks] = lds_rp<D>(smem, lo, ks, TILE_BYTES + blk_off);
+  }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    s = mfma32(qa[ks], kreg[ks], s);
+    dp = mfma32(da[ks], vreg[ks], dp);
+  }
+}
+
+// p = exp2(c s - lse2) on visible pairs (in s), dS = p (dP - delta) (in dp).  `masked` is
+// wave-uniform: only blocks on the causal diagonal or past the last row take the branch.
+SP_DEV void dkdv_softmax(f32x16& s, f32x16& dp, const float* lse_t, const float* del_t, int qb, int g, float c,
+                         bool masked, int rmin_rel, int rmax_rel) {
+  if (masked) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int r = 8 * (i >> 2) + 4 * g + (i & 3);
+      s[i] = ((r >= rmin_rel) & (r < rmax_rel)) ? s[i] : -INFINITY;      // exp2(-inf) = 0
+    }
+  }
+#pragma unroll
+  for (int i4 = 0; i4 < 4; ++i4) {
+    const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_t + qb * 32 + 8 * i4 + 4 * g);
+    const f32x4 d4 = *reinterpret_cast<const f32x4*>(del_t + qb * 32 + 8 * i4 + 4 * g);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int i = 4 * i4 + j;
+      const float p = exp2_fast(__builtin_fmaf(s[i], c, -l4[j]));
+      s[i] = p;
+      dp[i] = p * (dp[i] - d4[j]);
+    }
+  }
+}
+
+// dV^T += dO^T P, dK^T += Q^T dS for one 32-row block (transposed A operands from LDS).
+template <int D, int TILE_BYTES>
+SP_DEV void dkdv_accumulate(const char* smem, const LaneOffsets<D>& lo, int blk_off, const f32x16& p, const f32x16& ds,
+                            f32x16 (&dk)[D / 32], f32x16 (&dv)[D / 32]) {
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const bf16x8 pb = pack8(p, 8 * half);
+    const bf16x8 dsb = pack8(ds, 8 * half);
+    bf16x8 dot[D / 32], qt[D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) {
+      dot[db] = lds_tr<D>(smem, lo, db, TILE_BYTES + blk_off + half * 16 * D * 2);
+      qt[db] = lds_tr<D>(smem, lo, db, blk_off + half * 16 * D * 2);
+    }
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) {
+      dv[db] = mfma32(dot[db], pb, dv[db]);
+      dk[db] = mfma32(qt[db], dsb, dk[db]);
+    }
+  }
+}
+
+// All QB blocks of one staged query tile, software pipelined: the score MFMAs of block qb+1 are
+// issued before the softmax of block qb so the matrix pipe has work while the VALU runs.
+// rmin_tile = first row of the tile (relative) that sees this lane's key; rows_left = valid rows;
+// wave_rmin = the same for the wave's LAST key (wave-uniform): blocks starting at or after it need
+// no causal mask.
+template <int D, int BMQ>
+SP_DEV void dkdv_tile(const char* smem, const LaneOffsets<D>& lo, const float* lse_t, const float* del_t, int lane,
+                      const bf16x8 (&kreg)[D / 16], const bf16x8 (&vreg)[D / 16],
+                      f32x16 (&dk)[D / 32], f32x16 (&dv)[D / 32], float c, int rmin_tile, int wave_rmin, int rows_left) {
+  constexpr int QB = BMQ / 32, TILE_BYTES = BMQ * D * 2, BLK = 32 * D * 2;
+  const int g = lane >> 5;
+  f32x16 s_cur, dp_cur;
+  dkdv_scores<D, TILE_BYTES>(smem, lo, 0, kreg, vreg, s_cur, dp_cur);
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    f32x16 s_nxt, dp_nxt;
+    if (qb + 1 < QB) dkdv_scores<D, TILE_BYTES>(smem, lo, (qb + 1) * BLK, kreg, vreg, s_nxt, dp_nxt);
+    const bool masked = (wave_rmin > qb * 32) || (rows_left < qb * 32 + 32);
+    const int rmin = rmin_tile - qb * 32, left = rows_left - qb * 32;
+    const int rmin_rel = rmin < 0 ? 0 : (rmin > 32 ? 32 : rmin);
+    const int rmax_rel = left < 0 ? 0 : (left > 32 ? 32 : left);
+    dkdv_softmax(s_cur, dp_cur, lse_t, del_t, qb, g, c, masked, rmin_rel, rmax_rel);
+    dkdv_accumulate<D, TILE_BYTES>(smem, lo, qb * BLK, s_cur, dp_cur, dk, dv);
+    if (qb + 1 < QB) { s_cur = s_nxt; dp_cur = dp_nxt; }
+  }
+}
+
 template <int D, int NW, int BMQ>
 __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a) {
-  constexpr int BNK = NW * 32, KS = D / 16, DB = D / 32, QB = BMQ / 32, T = NW * 64;
+  constexpr int BNK = NW * 32, KS = D / 16, DB = D / 32, T = NW * 64;
   constexpr int TILE_BYTES = BMQ * D * 2;
-  constexpr int BUF_BYTES = 2 * TILE_BYTES + 2 * BMQ * 4;      // Q tile, dO tile, lse2[BMQ], delta[BMQ]
+  constexpr int BUF_BYTES = 2 * TILE_BYTES;                    // Q tile, dO tile (power of two)
+  static_assert((BUF_BYTES & (BUF_BYTES - 1)) == 0, "buffer toggle is an XOR");
   static_assert(BMQ <= T, "one thread per staged row statistic");
   extern __shared__ __attribute__((aligned(16))) char smem[];
+  float* stats = reinterpret_cast<float*>(smem + 2 * BUF_BYTES);   // [2 buffers][lse2[BMQ], delta[BMQ]]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ql = lane & 31;
   const int hk = blockIdx.y, b = blockIdx.z;
@@ -255,17 +364,19 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
   const int nq = nqt > qt0 ? nqt - qt0 : 0;
   const int total = nq * a.group;
   const float c = a.scale_log2e;
+  // first row (absolute, within the slice) that sees this lane's key
+  const int64_t rmin_abs = a.causal ? mykey - a.q_offset : 0;
+  const int64_t wave_rmin_abs = a.causal ? wkey0 + 31 - a.q_offset : 0;   // same for the wave's last key
 
-  TileStage<D, BMQ, T> q_stage, do_stage;
   float st_lse = 0.f, st_delta = 0.f;
-
-  auto issue = [&](int it) {
+  auto issue = [&](int it, int buf) {
     const int hh = it / nq, qt = qt0 + it % nq;
     const int h = hk * a.group + hh;
+    char* base = smem + buf * BUF_BYTES;
     const bf16_t* qb = a.q + (int64_t)b * a.q_stride_b + (int64_t)h * a.q_stride_h;
     const bf16_t* ob = a.d_out + (int64_t)b * a.do_stride_b + (int64_t)h * a.do_stride_h;
-    q_stage.issue(qb, a.q_stride_s, (int64_t)qt * BMQ, a.s_q - 1, tid);
-    do_stage.issue(ob, a.do_stride_s, (int64_t)qt * BMQ, a.s_q - 1, tid);
+    tile_load_async<D, BMQ, T>(base, qb, a.q_stride_s, (int64_t)qt * BMQ, a.s_q - 1, tid);
+    tile_load_async<D, BMQ, T>(base + TILE_BYTES, ob, a.do_stride_s, (int64_t)qt * BMQ, a.s_q - 1, tid);
     if (tid < BMQ) {
       int r = qt * BMQ + tid;
       r = r < a.s_q ? r : a.s_q - 1;
@@ -275,81 +386,39 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
       st_delta = a.delta[sidx];
     }
   };
-  auto commit = [&](int buf) {
-    char* base = smem + buf * BUF_BYTES;
-    q_stage.commit(base, tid);
-    do_stage.commit(base + TILE_BYTES, tid);
+  auto commit_stats = [&](int buf) {
     if (tid < BMQ) {
-      reinterpret_cast<float*>(base + 2 * TILE_BYTES)[tid] = st_lse;
-      reinterpret_cast<float*>(base + 2 * TILE_BYTES + BMQ * 4)[tid] = st_delta;
+      stats[buf * 2 * BMQ + tid] = st_lse;
+      stats[buf * 2 * BMQ + BMQ + tid] = st_delta;
     }
   };
 
-  if (total > 0) { issue(0); commit(0); }
+  LaneOffsets<D> lo;
+  lo.init(lane, 0);
+
+  if (total > 0) { issue(0, 0); commit_stats(0); }
+  wait_async();
   __syncthreads();
 
   for (int it = 0; it < total; ++it) {
     const int qt = qt0 + it % nq;
-    const char* base = smem + (it & 1) * BUF_BYTES;
-    const char* qtile = base;
-    const char* dotile = base + TILE_BYTES;
-    const float* lse_t = reinterpret_cast<const float*>(base + 2 * TILE_BYTES);
+    const float* lse_t = stats + (it & 1) * 2 * BMQ;
     const float* del_t = lse_t + BMQ;
     const bool more = (it + 1 < total);
-    if (more) issue(it + 1);
+    if (more) issue(it + 1, (it + 1) & 1);
 
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-      const int row0 = qt * BMQ + qb * 32;                     // first query row of this 32-block
-      // rows all before this wave's first key see none of its keys; rows all >= s_q do not exist
-      const bool skip = (a.causal && a.q_offset + row0 + 31 < wkey0) || row0 >= a.s_q;
-      if (!skip) {
-        f32x16 s, dp;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          bf16x8 qa = lds_read_rowpacked<D>(qtile, qb * 32 + ql, ks, g);
-          s = mfma32(qa, kreg[ks], s);
-        }
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          bf16x8 da = lds_read_rowpacked<D>(dotile, qb * 32 + ql, ks, g);
-          dp = mfma32(da, vreg[ks], dp);
-        }
-        const bool need_mask = (row0 + 32 > a.s_q) || (a.causal && wkey0 + 31 > a.q_offset + row0);
-#pragma unroll
-        for (int i4 = 0; i4 < 4; ++i4) {
-          const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_t + qb * 32 + 8 * i4 + 4 * g);
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(del_t + qb * 32 + 8 * i4 + 4 * g);
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int i = 4 * i4 + j;
-            float p = exp2_fast(__builtin_fmaf(s[i], c, -l4[j]));
-            if (need_mask) {
-              const int row = row0 + 8 * i4 + 4 * g + j;
-              const bool vis = row < a.s_q && (!a.causal || mykey <= a.q_offset + row);
-              p = vis ? p : 0.f;
-            }
-            s[i] = p;
-            dp[i] = p * (dp[i] - d4[j]);                      // dS
-          }
-        }
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          const bf16x8 pb = pack8(s, 8 * half);
-          const bf16x8 dsb = pack8(dp, 8 * half);
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            bf16x8 dot = lds_read_transposed<D>(dotile, qb * 32 + 16 * half, db, lane);
-            dv[db] = mfma32(dot, pb, dv[db]);
-            bf16x8 qt_ = lds_read_transposed<D>(qtile, qb * 32 + 16 * half, db, lane);
-            dk[db] = mfma32(qt_, dsb, dk[db]);
-          }
-        }
-      }
+    const int row0 = qt * BMQ;
+    {
+      // rows of this tile that see the lane's key / the wave's last key, clamped to [0, BMQ]
+      const int64_t rl = rmin_abs - row0, rw = wave_rmin_abs - row0;
+      const int rmin_tile = rl < 0 ? 0 : (rl > BMQ ? BMQ : (int)rl);
+      const int wave_rmin = rw < 0 ? 0 : (rw > BMQ ? BMQ : (int)rw);
+      dkdv_tile<D, BMQ>(smem, lo, lse_t, del_t, lane, kreg, vreg, dk, dv, c, rmin_tile, wave_rmin, a.s_q - row0);
     }
-    if (more) commit((it + 1) & 1);
+    lo.toggle(BUF_BYTES);
+
+    if (more) commit_stats((it + 1) & 1);
+    wait_async();
     __syncthreads();
   }
 
@@ -375,7 +444,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
 template <int D, int NW, int BMQ>
 static hipError_t launch_dkdv_t(const BwdArgs& a, int batch, hipStream_t st) {
   constexpr int BNK = NW * 32;
-  const size_t smem = (size_t)2 * (2 * BMQ * D * 2 + 2 * BMQ * 4);
+  const size_t smem = (size_t)2 * (2 * BMQ * D * 2) + 2 * 2 * BMQ * 4;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dkdv_kernel<D, NW, BMQ>),
@@ -391,8 +460,13 @@ static hipError_t launch_dkdv_t(const BwdArgs& a, int batch, hipStream_t st) {
 }
 
 hipError_t launch_bwd_dkdv(const BwdArgs& a, int batch, int head_dim, hipStream_t st) {
-  if (head_dim == 128) return launch_dkdv_t<128, 4, 64>(a, batch, st);
-  return launch_dkdv_t<64, 4, 64>(a, batch, st);
+  static const int variant = [] { const char* e = getenv("SLIMPIPE_DKDV_BMQ"); return e ? atoi(e) : 128; }();
+  if (head_dim == 128) {
+    if (variant == 64) return launch_dkdv_t<128, 4, 64>(a, batch, st);
+    return launch_dkdv_t<128, 4, 128>(a, batch, st);
+  }
+  if (variant == 64) return launch_dkdv_t<64, 4, 64>(a, batch, st);
+  return launch_dkdv_t<64, 4, 128>(a, batch, st);
 }
 
 }  // namespace slimpipe

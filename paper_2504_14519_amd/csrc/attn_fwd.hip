@@ -94,13 +94,17 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
       }
       const bool need_mask = (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
       if (need_mask) {
+        // last visible key of this lane's query, relative to the tile (may be < 0 or >= BN)
+        int64_t kmax = a.kv_end - 1;
+        if (a.causal && qpos < kmax) kmax = qpos;
+        kmax -= key0;
+        const int kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
 #pragma unroll
         for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
-            const int64_t key = key0 + kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-            const bool vis = key < a.kv_end && (!a.causal || key <= qpos);
-            s[kb][i] = vis ? s[kb][i] : -INFINITY;
+            const int key_rel = kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+            s[kb][i] = key_rel <= kmax_rel ? s[kb][i] : -INFINITY;
           }
       }
       float mx = -INFINITY;
