@@ -86,7 +86,8 @@ def main():
     dv_acc = torch.zeros((1, N, Hkv, D), device=dev, dtype=torch.float32)
     dk_out = torch.empty((1, N, Hkv, D), device=dev, dtype=torch.bfloat16)
     dv_out = torch.empty((1, N, Hkv, D), device=dev, dtype=torch.bfloat16)
-    ws = torch.empty(Hq * s * 4 + 256, device=dev, dtype=torch.uint8)
+    ws_bytes = sp.slimpipe_attn_workspace_bytes(sp.make_params(q[:, :s], k, outs[0], 0, 0, s, True, scale), True)
+    ws = torch.empty(ws_bytes, device=dev, dtype=torch.uint8)
 
     def qs(j):
         return slice(j * s, (j + 1) * s)

@@ -75,8 +75,9 @@ typedef struct slimpipe_attn_params {
  * backward needs).  No device access. */
 int slimpipe_attn_validate(const slimpipe_attn_params* p, int is_bwd);
 
-/* Bytes of device workspace the call needs (0 for forward; for backward one float per
- * (batch, q head, row) for delta = rowsum(d_out * out), rounded up to 256 bytes). */
+/* Bytes of device workspace the call needs (0 for forward; for backward two floats per
+ * (batch, q head, row): delta = rowsum(d_out * out) and lse in log2 units, each array rounded up
+ * to 256 bytes). */
 int slimpipe_attn_workspace_bytes(const slimpipe_attn_params* p, int is_bwd, size_t* bytes);
 
 /* Forward of one query slice against keys [kv_begin, kv_end) of the cached prefix

@@ -97,6 +97,7 @@ def make_params(q, k, out_like, q_offset, kv_begin, kv_end, causal, scale, out_d
     p.q_stride_b, p.q_stride_s, p.q_stride_h = q.stride(0), q.stride(1), q.stride(2)
     p.kv_stride_b, p.kv_stride_s, p.kv_stride_h = k.stride(0), k.stride(1), k.stride(2)
     p.o_stride_b, p.o_stride_s, p.o_stride_h = out_like.stride(0), out_like.stride(1), out_like.stride(2)
+    p.do_stride_b, p.do_stride_s, p.do_stride_h = p.o_stride_b, p.o_stride_s, p.o_stride_h   # backward overrides
     return p
 
 

@@ -14,10 +14,12 @@ namespace {
 bool stride_ok(int64_t s) { return s > 0 && (s % 8) == 0; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-size_t delta_bytes(const slimpipe_attn_params* p) {
+// one float array per row statistic (delta, lse in log2 units), each rounded up to 256 bytes
+size_t stat_bytes(const slimpipe_attn_params* p) {
   size_t n = (size_t)p->batch * (size_t)p->n_q_heads * (size_t)p->s_q * sizeof(float);
   return (n + 255) & ~(size_t)255;
 }
+size_t delta_bytes(const slimpipe_attn_params* p) { return 2 * stat_bytes(p); }
 
 
 // ---- optional per-kernel event timing -------------------------------------------------------
@@ -155,6 +157,7 @@ int slimpipe_attn_bwd(const slimpipe_attn_params* p, const void* q_slice, const 
   a.d_out = static_cast<const __bf16*>(d_out);
   a.lse = lse;
   a.delta = static_cast<float*>(workspace);
+  a.lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + stat_bytes(p));
   a.dq = dq; a.dk_acc = dk_acc; a.dv_acc = dv_acc;
   a.s_q = p->s_q; a.n_q_heads = p->n_q_heads; a.n_kv_heads = p->n_kv_heads;
   a.group = p->n_q_heads / p->n_kv_heads; a.causal = p->causal;

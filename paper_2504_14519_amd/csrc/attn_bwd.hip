@@ -15,13 +15,16 @@
 //     One workgroup owns a key row outright, so dK/dV are bit-reproducible.
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "kernels.hpp"
 #include "tile_common.hpp"
 
 namespace slimpipe {
 
 // ------------------------------------------------------------------------------------ delta
-// delta[b,h,r] = sum_d dO[b,r,h,d] * O[b,r,h,d].  One 16-byte chunk per lane, D/8 lanes per row.
+// delta[b,h,r] = sum_d dO[b,r,h,d] * O[b,r,h,d] and lse2 = lse * log2(e) (+inf for rows that saw no
+// key, which makes every p of the row exp2(-inf) = 0).  One 16-byte chunk per lane, D/8 lanes per row.
 template <int D>
 __global__ __launch_bounds__(256) void attn_delta_kernel(const BwdArgs a, int batch) {
   constexpr int NC = D / 8;
@@ -45,7 +48,12 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const BwdArgs a, int ba
   }
 #pragma unroll
   for (int w = NC / 2; w >= 1; w >>= 1) acc += __shfl_xor(acc, w, 64);
-  if (rh < total && c == 0) a.delta[((int64_t)b * a.n_q_heads + h) * a.s_q + r] = acc;
+  if (rh < total && c == 0) {
+    const int64_t sidx = ((int64_t)b * a.n_q_heads + h) * a.s_q + r;
+    a.delta[sidx] = acc;
+    const float l = a.lse[sidx];
+    a.lse2[sidx] = (l == -INFINITY) ? INFINITY : l * kLog2e;
+  }
 }
 
 hipError_t launch_delta(const BwdArgs& a, int batch, int head_dim, hipStream_t st) {
@@ -84,8 +92,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
     }
   }
   const int64_t stat = ((int64_t)b * a.n_q_heads + h) * a.s_q + myrow_c;
-  const float lse_raw = a.lse[stat];
-  const float lse2 = (lse_raw == -INFINITY) ? INFINITY : lse_raw * kLog2e;   // empty row -> p = 0
+  const float lse2 = a.lse2[stat];          // +inf for an empty row -> p = 0
   const float delta = a.delta[stat];
 
   const int64_t lo = a.kv_begin;
@@ -224,34 +231,52 @@ hipError_t launch_bwd_dq(const BwdArgs& a, int batch, int head_dim, hipStream_t 
 }
 
 // ------------------------------------------------------------------------------------ dk / dv
-// LDS map of the dk/dv kernel: two 2*TILE-byte buffers (Q tile, dO tile), each buffer a power of
-// two in size so that switching buffers is one XOR on the lane offsets; row statistics behind them.
+// The dk/dv kernel treats the query rows it has to visit (all query tiles that can see its keys,
+// for every head of the GQA group, in a fixed order) as ONE stream of 32-row blocks and runs a
+// software pipeline over that stream.  For block j:
+//   region X: score MFMAs of block j+1  ||  softmax of block j  ||  transposed operand reads of j
+//   region Y: accumulate MFMAs of block j  ||  score operand reads of block j+2
+// A wave issues in order, so the overlap has to be in the instruction stream itself; each region
+// is one scheduling region and the group barriers ask for "1 MFMA, then a few VALU / LDS reads".
+// Query tiles (BMQ rows of Q and dO) sit in a ring of three LDS buffers: while tile t is consumed,
+// tile t+1 is already resident (its first block's scores are computed ahead) and tile t+2 is in
+// flight, so one barrier per tile is enough.
 
-// One 32-row query block against the wave's 32 keys: S = Q K^T and dP = dO V^T (row-packed A
-// operands from LDS, K/V B operands from registers).  `blk_off` = qb*32 rows in bytes.
+#define SP_FENCE() __builtin_amdgcn_sched_barrier(0)
+// scheduling-group classes of __builtin_amdgcn_sched_group_barrier
+#define SP_SG_VALU 0x2
+#define SP_SG_MFMA 0x8
+#define SP_SG_DSRD 0x100
+
+// Operands of one 32-row query block for S = Q K^T and dP = dO V^T (row-packed reads).
+template <int D>
+struct ScoreOps { bf16x8 qa[D / 16], da[D / 16]; };
+
 template <int D, int TILE_BYTES>
-SP_DEV void dkdv_scores(const char* smem, const LaneOffsets<D>& lo, int blk_off,
-                        const bf16x8 (&kreg)[D / 16], const bf16x8 (&vreg)[D / 16], f32x16& s, f32x16& dp) {
-  bf16x8 qa[D / 16], da[D / 16];
+SP_DEV void dkdv_load_ops(const char* smem, const RpOffsets<D>& lo, int blk_off, ScoreOps<D>& o) {
 #pragma unroll
   for (int ks = 0; ks < D / 16; ++ks) {
-    qa[ks] = lds_rp<D>(smem, lo, ks, blk_off);
-    da[ks] = lds_rp<D>(smem, lo, ks, TILE_BYTES + blk_off);
+    o.qa[ks] = lds_rp<D>(smem, lo, ks, blk_off);
+    o.da[ks] = lds_rp<D>(smem, lo, ks, TILE_BYTES + blk_off);
   }
+}
+template <int D>
+SP_DEV void dkdv_scores(const ScoreOps<D>& o, const bf16x8 (&kreg)[D / 16], const bf16x8 (&vreg)[D / 16],
+                        f32x16& s, f32x16& dp) {
 #pragma unroll
   for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
 #pragma unroll
   for (int ks = 0; ks < D / 16; ++ks) {
-    s = mfma32(qa[ks], kreg[ks], s);
-    dp = mfma32(da[ks], vreg[ks], dp);
+    s = mfma32(o.qa[ks], kreg[ks], s);
+    dp = mfma32(o.da[ks], vreg[ks], dp);
   }
 }
 
-// p = exp2(c s - lse2) on visible pairs (in s), dS = p (dP - delta) (in dp).  `masked` is
-// wave-uniform: only blocks on the causal diagonal or past the last row take the branch.
+// p = exp2(c s - lse2) on visible pairs (in s), dS = p (dP - delta) (in dp).
+template <bool MASK>
 SP_DEV void dkdv_softmax(f32x16& s, f32x16& dp, const float* lse_t, const float* del_t, int qb, int g, float c,
-                         bool masked, int rmin_rel, int rmax_rel) {
-  if (masked) {
+                         int rmin_rel, int rmax_rel) {
+  if (MASK) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int r = 8 * (i >> 2) + 4 * g + (i & 3);
@@ -272,64 +297,141 @@ SP_DEV void dkdv_softmax(f32x16& s, f32x16& dp, const float* lse_t, const float*
   }
 }
 
-// dV^T += dO^T P, dK^T += Q^T dS for one 32-row block (transposed A operands from LDS).
+// Transposed operands of one 16-row half block for dV^T += dO^T P and dK^T += Q^T dS.
+template <int D>
+struct AccOps { bf16x8 dot[D / 32], qt[D / 32]; };
+
 template <int D, int TILE_BYTES>
-SP_DEV void dkdv_accumulate(const char* smem, const LaneOffsets<D>& lo, int blk_off, const f32x16& p, const f32x16& ds,
-                            f32x16 (&dk)[D / 32], f32x16 (&dv)[D / 32]) {
+SP_DEV void dkdv_load_acc(const char* smem, const TrOffsets<D>& lo, int half_off, AccOps<D>& o) {
 #pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    const bf16x8 pb = pack8(p, 8 * half);
-    const bf16x8 dsb = pack8(ds, 8 * half);
-    bf16x8 dot[D / 32], qt[D / 32];
+  for (int db = 0; db < D / 32; ++db) {
+    o.dot[db] = lds_tr<D>(smem, lo, db, TILE_BYTES + half_off);
+    o.qt[db] = lds_tr<D>(smem, lo, db, half_off);
+  }
+}
+template <int D>
+SP_DEV void dkdv_accumulate(const AccOps<D>& o, bf16x8 pb, bf16x8 dsb, f32x16 (&dk)[D / 32], f32x16 (&dv)[D / 32]) {
 #pragma unroll
-    for (int db = 0; db < D / 32; ++db) {
-      dot[db] = lds_tr<D>(smem, lo, db, TILE_BYTES + blk_off + half * 16 * D * 2);
-      qt[db] = lds_tr<D>(smem, lo, db, blk_off + half * 16 * D * 2);
-    }
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db) {
-      dv[db] = mfma32(dot[db], pb, dv[db]);
-      dk[db] = mfma32(qt[db], dsb, dk[db]);
-    }
+  for (int db = 0; db < D / 32; ++db) {
+    dv[db] = mfma32(o.dot[db], pb, dv[db]);
+    dk[db] = mfma32(o.qt[db], dsb, dk[db]);
   }
 }
 
-// All QB blocks of one staged query tile, software pipelined: the score MFMAs of block qb+1 are
-// issued before the softmax of block qb so the matrix pipe has work while the VALU runs.
-// rmin_tile = first row of the tile (relative) that sees this lane's key; rows_left = valid rows;
-// wave_rmin = the same for the wave's LAST key (wave-uniform): blocks starting at or after it need
-// no causal mask.
-template <int D, int BMQ>
-SP_DEV void dkdv_tile(const char* smem, const LaneOffsets<D>& lo, const float* lse_t, const float* del_t, int lane,
-                      const bf16x8 (&kreg)[D / 16], const bf16x8 (&vreg)[D / 16],
-                      f32x16 (&dk)[D / 32], f32x16 (&dv)[D / 32], float c, int rmin_tile, int wave_rmin, int rows_left) {
-  constexpr int QB = BMQ / 32, TILE_BYTES = BMQ * D * 2, BLK = 32 * D * 2;
-  const int g = lane >> 5;
-  f32x16 s_cur, dp_cur;
-  dkdv_scores<D, TILE_BYTES>(smem, lo, 0, kreg, vreg, s_cur, dp_cur);
+// The global->LDS traffic of the tile two steps ahead.  It is staged through registers (global
+// loads early in a tile, LDS writes at its end): the compiler must assume that an asynchronous
+// global->LDS copy aliases every later LDS read and would make the wave wait for it on the spot.
+struct DkdvDma {
+  const bf16_t* q;         // head base of Q
+  const bf16_t* dout;      // head base of dO
+  const float* lse2;       // head base of the row statistics
+  const float* delta;
+  int64_t q_stride_s, do_stride_s;
+  int row0, row_last;      // first row of the tile, last valid row of the slice
+  char* dst;               // LDS: Q tile, dO tile behind it
+  float* dst_stats;        // LDS: lse2[BMQ], delta[BMQ]
+};
+template <int D, int BMQ, int T>
+struct DkdvStage {
+  static constexpr int NC = D / 8, PASSES = BMQ * NC / T, PARTS = 4;
+  static constexpr int part_of(int n) { return PASSES >= PARTS ? n % PARTS : n * (PARTS / PASSES); }
+  u32x4 q[PASSES], o[PASSES];
+  float stat;
+  // Part P of the global loads of one tile.  The L1 path moves 64 bytes per clock for the whole CU
+  // and a wave stalls at issue while it is busy, so the parts are spread over the pipeline steps.
+  template <int P>
+  SP_DEV void load_part(const DkdvDma& j, int tid) {
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    f32x16 s_nxt, dp_nxt;
-    if (qb + 1 < QB) dkdv_scores<D, TILE_BYTES>(smem, lo, (qb + 1) * BLK, kreg, vreg, s_nxt, dp_nxt);
-    const bool masked = (wave_rmin > qb * 32) || (rows_left < qb * 32 + 32);
-    const int rmin = rmin_tile - qb * 32, left = rows_left - qb * 32;
-    const int rmin_rel = rmin < 0 ? 0 : (rmin > 32 ? 32 : rmin);
-    const int rmax_rel = left < 0 ? 0 : (left > 32 ? 32 : left);
-    dkdv_softmax(s_cur, dp_cur, lse_t, del_t, qb, g, c, masked, rmin_rel, rmax_rel);
-    dkdv_accumulate<D, TILE_BYTES>(smem, lo, qb * BLK, s_cur, dp_cur, dk, dv);
-    if (qb + 1 < QB) { s_cur = s_nxt; dp_cur = dp_nxt; }
+    for (int n = 0; n < PASSES; ++n) {
+      if (part_of(n) != P) continue;
+      const int id = tid + n * T;
+      const int r = id / NC, c = id % NC;
+      int64_t gr = j.row0 + r;
+      gr = gr < j.row_last ? gr : j.row_last;
+      q[n] = *reinterpret_cast<const u32x4*>(j.q + gr * j.q_stride_s + c * 8);
+      o[n] = *reinterpret_cast<const u32x4*>(j.dout + gr * j.do_stride_s + c * 8);
+    }
+    if (P == PARTS - 1 && tid < 2 * BMQ) {     // threads [0,BMQ): lse2 rows, [BMQ,2BMQ): delta rows
+      int r = j.row0 + (tid & (BMQ - 1));
+      r = r < j.row_last ? r : j.row_last;
+      stat = (tid < BMQ ? j.lse2 : j.delta)[r];
+    }
   }
+  SP_DEV void load(const DkdvDma& j, int tid) {
+    load_part<0>(j, tid); load_part<1>(j, tid); load_part<2>(j, tid); load_part<3>(j, tid);
+  }
+  SP_DEV void store(char* dst, float* dst_stats, int tid) const {
+#pragma unroll
+    for (int n = 0; n < PASSES; ++n) {
+      const int id = tid + n * T;
+      const int r = id / NC, c = id % NC;
+      *reinterpret_cast<u32x4*>(dst + tile_off<D>(r, c)) = q[n];
+      *reinterpret_cast<u32x4*>(dst + BMQ * D * 2 + tile_off<D>(r, c)) = o[n];
+    }
+    if (tid < 2 * BMQ) dst_stats[tid] = stat;
+  }
+};
+
+// One pipeline step: consumes the scores (s, dp) of block (tile t, block qb), produces the scores of
+// the following block into (s_n, dp_n) from `ops`, then refills `ops` with the block after that.
+//   cur: tile t (transposed reads), nxt_blk_off: where block j+1 .. the refill reads from (row-packed,
+//   through lo_rp which already points at the right tile).
+template <int D, int BMQ, int T, bool MASK, int QB_IDX>
+SP_DEV void dkdv_step(const char* smem, const TrOffsets<D>& lo_tr, const RpOffsets<D>& lo_rp, int refill_off,
+                      DkdvStage<D, BMQ, T>& stage, const DkdvDma& dma, char* store_dst, float* store_stats, int tid,
+                      const float* lse_t, const float* del_t, int g, float c, int rmin_tile, int rows_left,
+                      const bf16x8 (&kreg)[D / 16], const bf16x8 (&vreg)[D / 16], ScoreOps<D>& ops,
+                      f32x16& s, f32x16& dp, f32x16& s_n, f32x16& dp_n, f32x16 (&dk)[D / 32], f32x16 (&dv)[D / 32]) {
+  constexpr int TILE_BYTES = BMQ * D * 2, BLK = 32 * D * 2, HALF = 16 * D * 2;
+  constexpr int NM = 2 * (D / 16);
+  AccOps<D> acc0, acc1;
+  constexpr int qb = QB_IDX;
+  SP_FENCE();
+  // ---- region X
+  if (QB_IDX == 1) { stage.template load_part<0>(dma, tid); stage.template load_part<1>(dma, tid); }
+  dkdv_scores<D>(ops, kreg, vreg, s_n, dp_n);
+  int rmin_rel = 0, rmax_rel = 32;
+  if (MASK) {
+    const int rmin = rmin_tile - qb * 32, left = rows_left - qb * 32;
+    rmin_rel = rmin < 0 ? 0 : (rmin > 32 ? 32 : rmin);
+    rmax_rel = left < 0 ? 0 : (left > 32 ? 32 : left);
+  }
+  dkdv_softmax<MASK>(s, dp, lse_t, del_t, qb, g, c, rmin_rel, rmax_rel);
+  const bf16x8 pb0 = pack8(s, 0), pb1 = pack8(s, 8);
+  const bf16x8 ds0 = pack8(dp, 0), ds1 = pack8(dp, 8);
+  dkdv_load_acc<D, TILE_BYTES>(smem, lo_tr, qb * BLK, acc0);
+  dkdv_load_acc<D, TILE_BYTES>(smem, lo_tr, qb * BLK + HALF, acc1);
+#pragma unroll
+  for (int i = 0; i < NM; ++i) {
+    __builtin_amdgcn_sched_group_barrier(SP_SG_MFMA, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(SP_SG_VALU, 7, 0);
+    __builtin_amdgcn_sched_group_barrier(SP_SG_DSRD, 3, 0);
+  }
+  SP_FENCE();
+  // ---- region Y
+  if (QB_IDX == 1) { stage.template load_part<2>(dma, tid); stage.template load_part<3>(dma, tid); }
+  if (QB_IDX == 0) stage.store(store_dst, store_stats, tid);
+  dkdv_accumulate<D>(acc0, pb0, ds0, dk, dv);
+  dkdv_accumulate<D>(acc1, pb1, ds1, dk, dv);
+  dkdv_load_ops<D, TILE_BYTES>(smem, lo_rp, refill_off, ops);
+#pragma unroll
+  for (int i = 0; i < NM; ++i) {
+    __builtin_amdgcn_sched_group_barrier(SP_SG_MFMA, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(SP_SG_DSRD, 1, 0);
+  }
+  SP_FENCE();
 }
 
 template <int D, int NW, int BMQ>
 __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a) {
   constexpr int BNK = NW * 32, KS = D / 16, DB = D / 32, T = NW * 64;
-  constexpr int TILE_BYTES = BMQ * D * 2;
-  constexpr int BUF_BYTES = 2 * TILE_BYTES;                    // Q tile, dO tile (power of two)
-  static_assert((BUF_BYTES & (BUF_BYTES - 1)) == 0, "buffer toggle is an XOR");
-  static_assert(BMQ <= T, "one thread per staged row statistic");
+  constexpr int TILE_BYTES = BMQ * D * 2, BLK = 32 * D * 2;
+  constexpr int BUF_BYTES = 2 * TILE_BYTES;                    // Q tile, dO tile
+  constexpr int NBUF = 3;
+  static_assert(BMQ == 64, "the pipeline below is written for two 32-row blocks per tile");
+  static_assert(2 * BMQ <= T, "one thread per staged row statistic");
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  float* stats = reinterpret_cast<float*>(smem + 2 * BUF_BYTES);   // [2 buffers][lse2[BMQ], delta[BMQ]]
+  float* stats = reinterpret_cast<float*>(smem + NBUF * BUF_BYTES);   // [NBUF][lse2[BMQ], delta[BMQ]]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ql = lane & 31;
   const int hk = blockIdx.y, b = blockIdx.z;
@@ -354,72 +456,141 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
 #pragma unroll
     for (int i = 0; i < 16; ++i) { dk[db][i] = 0.f; dv[db][i] = 0.f; }
 
-  // query tiles that can see this key tile
-  int qt0 = 0;
+  // Query tiles that can see this key tile: [qt0, nqt).  Tiles that need a mask (they straddle the
+  // causal diagonal of this key tile, or hold rows past s_q) are walked first, for every head of the
+  // group, then the unmasked rest; the order is fixed, so the sums are reproducible.
+  const int nqt = (a.s_q + BMQ - 1) / BMQ;
+  int qt0 = 0, qtm = 0;                                      // masked: [qt0, qtm) (+ a partial last tile)
   if (a.causal && tile_key0 > a.q_offset) {
     const int64_t first = tile_key0 - a.q_offset;            // first row that sees tile_key0
-    qt0 = first >= a.s_q ? (a.s_q + BMQ - 1) / BMQ : (int)(first / BMQ);
+    qt0 = first >= a.s_q ? nqt : (int)(first / BMQ);
   }
-  const int nqt = (a.s_q + BMQ - 1) / BMQ;
-  const int nq = nqt > qt0 ? nqt - qt0 : 0;
-  const int total = nq * a.group;
+  if (a.causal) {
+    const int64_t full = tile_key0 + BNK - 1 - a.q_offset;   // first row that sees every key of the tile
+    qtm = full <= 0 ? 0 : (full >= a.s_q ? nqt : (int)((full + BMQ - 1) / BMQ));
+  }
+  if (qtm < qt0) qtm = qt0;
+  const bool partial_last = (a.s_q % BMQ) != 0 && nqt - 1 >= qtm;
+  const int nm = (qtm - qt0) + (partial_last ? 1 : 0);       // masked tiles per head
+  const int nu = (nqt - qtm) - (partial_last ? 1 : 0);       // unmasked tiles per head
+  const int total_m = nm * a.group, total = (nm + nu) * a.group;
   const float c = a.scale_log2e;
   // first row (absolute, within the slice) that sees this lane's key
   const int64_t rmin_abs = a.causal ? mykey - a.q_offset : 0;
-  const int64_t wave_rmin_abs = a.causal ? wkey0 + 31 - a.q_offset : 0;   // same for the wave's last key
 
-  float st_lse = 0.f, st_delta = 0.f;
-  auto issue = [&](int it, int buf) {
-    const int hh = it / nq, qt = qt0 + it % nq;
+  // sequence index -> (head of the group, query tile)
+  auto locate = [&](int seq, int& hh, int& qt) {
+    if (seq < total_m) {
+      hh = seq / nm;
+      const int r = seq % nm;
+      qt = (r < qtm - qt0) ? qt0 + r : nqt - 1;
+    } else {
+      const int u = seq - total_m;
+      hh = u / nu;
+      qt = qtm + u % nu;
+    }
+  };
+
+  auto make_dma = [&](int seq, int buf) {
+    int hh, qt;
+    locate(seq, hh, qt);
     const int h = hk * a.group + hh;
-    char* base = smem + buf * BUF_BYTES;
-    const bf16_t* qb = a.q + (int64_t)b * a.q_stride_b + (int64_t)h * a.q_stride_h;
-    const bf16_t* ob = a.d_out + (int64_t)b * a.do_stride_b + (int64_t)h * a.do_stride_h;
-    tile_load_async<D, BMQ, T>(base, qb, a.q_stride_s, (int64_t)qt * BMQ, a.s_q - 1, tid);
-    tile_load_async<D, BMQ, T>(base + TILE_BYTES, ob, a.do_stride_s, (int64_t)qt * BMQ, a.s_q - 1, tid);
-    if (tid < BMQ) {
-      int r = qt * BMQ + tid;
-      r = r < a.s_q ? r : a.s_q - 1;
-      const int64_t sidx = ((int64_t)b * a.n_q_heads + h) * a.s_q + r;
-      const float l = a.lse[sidx];
-      st_lse = (l == -INFINITY) ? INFINITY : l * kLog2e;
-      st_delta = a.delta[sidx];
-    }
+    DkdvDma j;
+    j.q = a.q + (int64_t)b * a.q_stride_b + (int64_t)h * a.q_stride_h;
+    j.dout = a.d_out + (int64_t)b * a.do_stride_b + (int64_t)h * a.do_stride_h;
+    j.lse2 = a.lse2 + ((int64_t)b * a.n_q_heads + h) * a.s_q;
+    j.delta = a.delta + ((int64_t)b * a.n_q_heads + h) * a.s_q;
+    j.q_stride_s = a.q_stride_s;
+    j.do_stride_s = a.do_stride_s;
+    j.row0 = qt * BMQ;
+    j.row_last = a.s_q - 1;
+    j.dst = smem + buf * BUF_BYTES;
+    j.dst_stats = stats + buf * 2 * BMQ;
+    return j;
   };
-  auto commit_stats = [&](int buf) {
-    if (tid < BMQ) {
-      stats[buf * 2 * BMQ + tid] = st_lse;
-      stats[buf * 2 * BMQ + BMQ + tid] = st_delta;
+  if (total > 0) {
+    // ---- prologue: tiles 0 and 1 resident, scores of block 0 computed, operands of block 1 loaded
+    DkdvStage<D, BMQ, T> stage;
+    // tiles 0 and 1 go to LDS, tile 2 waits in the staging registers (tile indices past the end of
+    // the stream are clamped: the last tile is fetched again and nobody reads it)
+    for (int t = 0; t < 3; ++t) {
+      const int tt = t < total ? t : total - 1;
+      const DkdvDma j = make_dma(tt, t);
+      stage.load(j, tid);
+      if (t < 2) stage.store(smem + t * BUF_BYTES, stats + t * 2 * BMQ, tid);
     }
-  };
-
-  LaneOffsets<D> lo;
-  lo.init(lane, 0);
-
-  if (total > 0) { issue(0, 0); commit_stats(0); }
-  wait_async();
-  __syncthreads();
-
-  for (int it = 0; it < total; ++it) {
-    const int qt = qt0 + it % nq;
-    const float* lse_t = stats + (it & 1) * 2 * BMQ;
-    const float* del_t = lse_t + BMQ;
-    const bool more = (it + 1 < total);
-    if (more) issue(it + 1, (it + 1) & 1);
-
-    const int row0 = qt * BMQ;
-    {
-      // rows of this tile that see the lane's key / the wave's last key, clamped to [0, BMQ]
-      const int64_t rl = rmin_abs - row0, rw = wave_rmin_abs - row0;
-      const int rmin_tile = rl < 0 ? 0 : (rl > BMQ ? BMQ : (int)rl);
-      const int wave_rmin = rw < 0 ? 0 : (rw > BMQ ? BMQ : (int)rw);
-      dkdv_tile<D, BMQ>(smem, lo, lse_t, del_t, lane, kreg, vreg, dk, dv, c, rmin_tile, wave_rmin, a.s_q - row0);
-    }
-    lo.toggle(BUF_BYTES);
-
-    if (more) commit_stats((it + 1) & 1);
-    wait_async();
     __syncthreads();
+
+    TrOffsets<D> lo_tr;      // tile being consumed
+    RpOffsets<D> lo_rp;      // tile the score operands are read from
+    lo_tr.init(lane, 0);
+    lo_rp.init(lane, 0);
+    ScoreOps<D> ops;
+    f32x16 sA, dpA, sB, dpB;
+    dkdv_load_ops<D, TILE_BYTES>(smem, lo_rp, 0, ops);
+    dkdv_scores<D>(ops, kreg, vreg, sA, dpA);
+    dkdv_load_ops<D, TILE_BYTES>(smem, lo_rp, BLK, ops);
+    lo_rp.add(BUF_BYTES);    // from now on: one tile ahead of lo_tr
+
+    int cur = 0;             // ring slot of the tile being consumed
+#ifdef SLIMPIPE_TRACE
+    long long tr_wait = 0, tr_issue = 0, tr_s0 = 0, tr_s1 = 0, tr_t0 = clock64(), tr_w0 = wall_clock64();
+#define TR_MARK(var) { long long _n = clock64(); var += _n - tr_last; tr_last = _n; }
+#else
+#define TR_MARK(var)
+#endif
+    auto tile_body = [&](int seq, auto mask_tag) {
+      constexpr bool MASK = decltype(mask_tag)::value;
+#ifdef SLIMPIPE_TRACE
+      long long tr_last = clock64();
+#endif
+      // tile seq+1 is written (it was stored one tile ago), every wave is done with tile seq-1
+      if (seq > 0) __syncthreads();
+      TR_MARK(tr_wait)
+      // the tile two steps ahead goes into the slot tile seq-1 just left; past the end of the stream
+      // the last tile is fetched again (nobody reads it) so that the steps stay branch-free
+      const int free_slot = cur == 0 ? NBUF - 1 : cur - 1;
+      // tile seq+2, loaded during the second step of tile seq-1, goes into the slot that tile just left
+      // (written during the first step below); the loads of tile seq+3 are issued in the second step
+      const DkdvDma dma = make_dma(seq + 3 < total ? seq + 3 : total - 1, 0);
+      TR_MARK(tr_issue)
+      const float* lse_t = stats + cur * 2 * BMQ;
+      int rmin_tile = 0, rows_left = BMQ;
+      if (MASK) {
+        int hh, qt;
+        locate(seq, hh, qt);
+        const int row0 = qt * BMQ;
+        const int64_t rl = rmin_abs - row0;
+        rmin_tile = rl < 0 ? 0 : (rl > BMQ ? BMQ : (int)rl);
+        rows_left = a.s_q - row0;
+      }
+      // block 0 of the tile: next scores = block 1 of this tile (ops already hold it);
+      // refill ops with block 0 of the next tile
+      dkdv_step<D, BMQ, T, MASK, 0>(smem, lo_tr, lo_rp, 0, stage, dma, smem + free_slot * BUF_BYTES, stats + free_slot * 2 * BMQ, tid, lse_t, lse_t + BMQ, g, c,
+                                 rmin_tile, rows_left, kreg, vreg, ops, sA, dpA, sB, dpB, dk, dv);
+      TR_MARK(tr_s0)
+      // block 1: next scores = block 0 of the next tile; refill with block 1 of the next tile
+      dkdv_step<D, BMQ, T, MASK, 1>(smem, lo_tr, lo_rp, BLK, stage, dma, smem + free_slot * BUF_BYTES, stats + free_slot * 2 * BMQ, tid, lse_t, lse_t + BMQ, g, c,
+                                 rmin_tile, rows_left, kreg, vreg, ops, sB, dpB, sA, dpA, dk, dv);
+      TR_MARK(tr_s1)
+      // advance the ring
+      const int step_tr = (cur == NBUF - 1) ? -(NBUF - 1) * BUF_BYTES : BUF_BYTES;
+      const int step_rp = (cur == NBUF - 2) ? -(NBUF - 1) * BUF_BYTES : BUF_BYTES;
+      lo_tr.add(step_tr);
+      lo_rp.add(step_rp);
+      cur = (cur == NBUF - 1) ? 0 : cur + 1;
+    };
+
+    int seq = 0;
+    for (; seq < total_m; ++seq) tile_body(seq, std::true_type{});     // masked tiles
+    for (; seq < total; ++seq) tile_body(seq, std::false_type{});      // unmasked tiles: the bulk
+#ifdef SLIMPIPE_TRACE
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {
+      long long* dbg = reinterpret_cast<long long*>(a.lse2 + (int64_t)a.n_q_heads * a.s_q);   // behind the workspace proper
+      dbg[0] = tr_wait; dbg[1] = tr_issue; dbg[2] = tr_s0; dbg[3] = tr_s1;
+      dbg[4] = clock64() - tr_t0; dbg[5] = wall_clock64() - tr_w0; dbg[6] = total;
+    }
+#endif
   }
 
   if (mykey < a.kv_end) {
@@ -444,7 +615,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
 template <int D, int NW, int BMQ>
 static hipError_t launch_dkdv_t(const BwdArgs& a, int batch, hipStream_t st) {
   constexpr int BNK = NW * 32;
-  const size_t smem = (size_t)2 * (2 * BMQ * D * 2) + 2 * 2 * BMQ * 4;
+  const size_t smem = (size_t)3 * (2 * BMQ * D * 2) + 3 * 2 * BMQ * 4;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dkdv_kernel<D, NW, BMQ>),
@@ -460,13 +631,8 @@ static hipError_t launch_dkdv_t(const BwdArgs& a, int batch, hipStream_t st) {
 }
 
 hipError_t launch_bwd_dkdv(const BwdArgs& a, int batch, int head_dim, hipStream_t st) {
-  static const int variant = [] { const char* e = getenv("SLIMPIPE_DKDV_BMQ"); return e ? atoi(e) : 128; }();
-  if (head_dim == 128) {
-    if (variant == 64) return launch_dkdv_t<128, 4, 64>(a, batch, st);
-    return launch_dkdv_t<128, 4, 128>(a, batch, st);
-  }
-  if (variant == 64) return launch_dkdv_t<64, 4, 64>(a, batch, st);
-  return launch_dkdv_t<64, 4, 128>(a, batch, st);
+  if (head_dim == 128) return launch_dkdv_t<128, 4, 64>(a, batch, st);
+  return launch_dkdv_t<64, 4, 64>(a, batch, st);
 }
 
 }  // namespace slimpipe

@@ -26,7 +26,8 @@ struct BwdArgs {
   const __bf16* out;
   const __bf16* d_out;
   const float* lse;
-  float* delta;            // workspace [batch, n_q_heads, s_q]
+  float* delta;            // workspace [batch, n_q_heads, s_q]: rowsum(dO * O)
+  float* lse2;             // workspace [batch, n_q_heads, s_q]: lse * log2(e), +inf where lse = -inf
   void* dq;
   float* dk_acc;
   float* dv_acc;

@@ -103,42 +103,49 @@ SP_DEV bf16x8 lds_read_transposed(const char* tile, int row0, int db, int lane) 
 // kernel is (one of these registers) + (compile-time constant): the constant goes into the
 // instruction's offset field and no address arithmetic is left in the loops.
 template <int D>
-struct LaneOffsets {
-  int rp[D / 16];       // row-packed: row = lane & 31, chunk 2*ks + g
-  int tr[D / 32][2];    // transposed: rows 4g + j/4 (+8 for the second read), column block db
+struct RpOffsets {       // row-packed: row = lane & 31, chunk 2*ks + g
+  int off[D / 16];
   SP_DEV void init(int lane, int base) {
     const int g = lane >> 5, ql = lane & 31;
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) rp[ks] = base + tile_off<D>(ql, 2 * ks + g);
+    for (int ks = 0; ks < D / 16; ++ks) off[ks] = base + tile_off<D>(ql, 2 * ks + g);
+  }
+  SP_DEV void add(int delta) {
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) off[ks] += delta;
+  }
+};
+template <int D>
+struct TrOffsets {       // transposed: rows 4g + j/4 (+8 for the second read), column block db
+  int off[D / 32][2];
+  SP_DEV void init(int lane, int base) {
     const int j = lane & 15, b = lane >> 4;
     const int row = ((b >> 1) << 2) + (j >> 2);
     const int sub = (j & 1) << 3;
 #pragma unroll
     for (int db = 0; db < D / 32; ++db) {
       const int chunk = 4 * db + 2 * (b & 1) + ((j & 3) >> 1);
-      tr[db][0] = base + tile_off<D>(row, chunk) + sub;
-      tr[db][1] = base + tile_off<D>(row + 8, chunk) + sub;
+      off[db][0] = base + tile_off<D>(row, chunk) + sub;
+      off[db][1] = base + tile_off<D>(row + 8, chunk) + sub;
     }
   }
-  SP_DEV void toggle(int mask) {
+  SP_DEV void add(int delta) {
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) rp[ks] ^= mask;
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db) { tr[db][0] ^= mask; tr[db][1] ^= mask; }
+    for (int db = 0; db < D / 32; ++db) { off[db][0] += delta; off[db][1] += delta; }
   }
 };
 
-// Reads through LaneOffsets; `smem` is the start of dynamic LDS, `const_off` a compile-time byte offset
-// (tile selector + 16-row block * row bytes).
+// Reads through the lane offsets; `smem` is the start of dynamic LDS, `const_off` a compile-time
+// byte offset (tile selector + 16-row block * row bytes).
 template <int D>
-SP_DEV bf16x8 lds_rp(const char* smem, const LaneOffsets<D>& lo, int ks, int const_off) {
-  return *reinterpret_cast<const bf16x8*>(smem + lo.rp[ks] + const_off);
+SP_DEV bf16x8 lds_rp(const char* smem, const RpOffsets<D>& lo, int ks, int const_off) {
+  return *reinterpret_cast<const bf16x8*>(smem + lo.off[ks] + const_off);
 }
 template <int D>
-SP_DEV bf16x8 lds_tr(const char* smem, const LaneOffsets<D>& lo, int db, int const_off) {
+SP_DEV bf16x8 lds_tr(const char* smem, const TrOffsets<D>& lo, int db, int const_off) {
   typedef bf16x4 __attribute__((address_space(3))) * lds_v4_ptr;
-  bf16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4_ptr)(smem + lo.tr[db][0] + const_off));
-  bf16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4_ptr)(smem + lo.tr[db][1] + const_off));
+  bf16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4_ptr)(smem + lo.off[db][0] + const_off));
+  bf16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4_ptr)(smem + lo.off[db][1] + const_off));
   bf16x8 r;
   r[0] = a[0]; r[1] = a[1]; r[2] = a[2]; r[3] = a[3];
   r[4] = b[0]; r[5] = b[1]; r[6] = b[2]; r[7] = b[3];
@@ -204,6 +211,26 @@ SP_DEV void tile_load_async(char* tile, const bf16_t* base, int64_t row_stride, 
                                      (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
   }
 }
+// One pass (THREADS chunks = THREADS/NC rows) of the same staging, so that a kernel can spread the
+// passes of a tile over its compute phase instead of issuing them back to back.
+template <int D, int THREADS>
+SP_DEV void tile_load_async_pass(char* tile, const bf16_t* base, int64_t row_stride, int64_t row0, int64_t row_last,
+                                 int tid, int n) {
+  constexpr int NC = D / 8;
+  const int wave = tid >> 6;
+  const int id = tid + n * THREADS;
+  const int r = id / NC, p = id % NC;
+  int c;
+  if constexpr (D == 128) c = ((((p >> 2) ^ r) & 3) << 2) | (((p & 3) ^ (r >> 2)) & 3);
+  else c = (p ^ r) & (NC - 1);
+  int64_t gr = row0 + r;
+  gr = gr < row_last ? gr : row_last;
+  const bf16_t* src = base + gr * row_stride + c * 8;
+  char* dst = tile + (n * THREADS + wave * 64) * 16;            // wave-uniform
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                   (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+}
+
 // vmcnt(0), other counters untouched (gfx9 encoding: vmcnt[3:0]|[15:14], expcnt[6:4], lgkmcnt[11:8]).
 SP_DEV void wait_async() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
