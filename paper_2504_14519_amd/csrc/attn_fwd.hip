@@ -1,27 +1,136 @@
 // Forward of slice-wise causal attention over a key range (paper Sec. 4.1.2; partial ranges and
 // the normaliser that travels with the output: Sec. 4.2.2, Sec. 5).
 //
-// One workgroup = NW wavefronts, each owning 32 query rows of one head.  The key range is walked
-// in tiles of BN keys staged in LDS (double buffered).  Per tile and wave:
+// One workgroup = 8 wavefronts, each owning 32 query rows of one head.  The key range is walked
+// in tiles of BN keys staged in LDS.  Per tile and wave:
 //   S^T = K Q^T        A = K rows from LDS (row-packed), B = Q held in registers
 //   online softmax     the C layout gives every lane ONE query column, so the row max / row sum
 //                      are in-lane reductions plus one exchange between the two half-waves
 //   O^T += V^T P^T     A = V through the transposed LDS read, B = P straight from the C registers
 // Scores and probabilities never leave registers.
+//
+// Schedule.  A wave alternates a matrix phase  M(t): O += P(t) V(t), S(t+1) = K(t+1) Q^T  with a
+// vector phase  V(t): P(t) = softmax(S(t)).  A SIMD hosts two waves of the workgroup; waves 0-3
+// (group A) and waves 4-7 (group B) run the same sequence one phase apart, with one workgroup
+// barrier per phase, so that on every SIMD one wave feeds the matrix pipe while the other runs the
+// softmax.  The pair (V(t), K(t+1)) that M(t) needs lives in one of two LDS buffer sets; the pair
+// after it is fetched to registers at the start of an even phase and written to the other set at
+// the end of the following odd phase.
 #include "kernels.hpp"
 #include "tile_common.hpp"
 
 namespace slimpipe {
 
+// End of a phase: nothing may be scheduled across it (the point of the two groups is that the
+// vector work of one wave runs while the OTHER wave of the SIMD has the matrix pipe).
+SP_DEV void phase_end() {
+  __builtin_amdgcn_sched_barrier(0);
+  __syncthreads();
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int D, int BN>
+struct FwdState {
+  static constexpr int KS = D / 16, DB = D / 32, KB = BN / 32;
+  bf16x8 qreg[KS];
+  f32x16 o[DB];
+  f32x16 s[KB];
+  bf16x8 p[KB][2];
+  float m_run, l_run;
+};
+
+// S(t)^T = K(t) Q^T for this wave's 32 queries.
+template <int D, int BN>
+SP_DEV void fwd_scores(const char* smem, const RpOffsets<D>& lo_k, FwdState<D, BN>& st) {
+#pragma unroll
+  for (int kb = 0; kb < BN / 32; ++kb) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) st.s[kb][i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+      const bf16x8 ka = lds_rp<D>(smem, lo_k, ks, kb * 32 * D * 2);
+      st.s[kb] = mfma32(ka, st.qreg[ks], st.s[kb]);
+    }
+  }
+}
+
+// O^T += V(t)^T P(t)^T.
+template <int D, int BN>
+SP_DEV void fwd_pv(const char* smem, const TrOffsets<D>& lo_v, FwdState<D, BN>& st) {
+#pragma unroll
+  for (int kb = 0; kb < BN / 32; ++kb)
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db) {
+        const bf16x8 va = lds_tr<D>(smem, lo_v, db, (kb * 32 + 16 * half) * D * 2);
+        st.o[db] = mfma32(va, st.p[kb][half], st.o[db]);
+      }
+}
+
+// P(t) = online softmax of S(t); rescales O and the running sum when a row maximum moves.
+// kmax_rel: last visible key of this lane's query relative to the tile (>= BN: no mask needed).
+template <int D, int BN>
+SP_DEV void fwd_softmax(FwdState<D, BN>& st, float c, bool need_mask, int kmax_rel, int g) {
+  constexpr int KB = BN / 32, DB = D / 32;
+  if (need_mask) {
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key_rel = kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+        st.s[kb][i] = key_rel <= kmax_rel ? st.s[kb][i] : -INFINITY;
+      }
+  }
+  float mx = -INFINITY;
+#pragma unroll
+  for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, st.s[kb][i]);
+  mx = xhalf_max(mx);
+  const float m_new = fmaxf(st.m_run, mx * c);
+  const float m_eff = (m_new == -INFINITY) ? 0.f : m_new;
+  // rescale only when some row of the wave moved its maximum (rare once a few tiles are in)
+  if (__builtin_amdgcn_ballot_w64(m_new != st.m_run) != 0) {
+    const float alpha = exp2_fast(st.m_run - m_eff);     // m_run = -inf -> 0
+    st.l_run *= alpha;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) st.o[db][i] *= alpha;
+  }
+  st.m_run = m_new;
+  float l_add = 0.f;
+#pragma unroll
+  for (int kb = 0; kb < KB; ++kb) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float p = exp2_fast(__builtin_fmaf(st.s[kb][i], c, -m_eff));
+      st.s[kb][i] = p;
+      l_add += p;
+    }
+    st.p[kb][0] = pack8(st.s[kb], 0);
+    st.p[kb][1] = pack8(st.s[kb], 8);
+    // pin the values here: without a use the optimiser sinks this arithmetic past the phase barrier
+    // into the matrix phase of the same wave
+    asm volatile("" : "+v"(st.p[kb][0]), "+v"(st.p[kb][1]));
+  }
+  st.l_run += l_add;
+  asm volatile("" : "+v"(st.l_run));
+}
+
 template <int D, int NW, int BN>
 __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
-  constexpr int BM = NW * 32, KS = D / 16, DB = D / 32, KB = BN / 32, T = NW * 64;
+  static_assert(NW == 8, "two groups of four waves");
+  constexpr int BM = NW * 32, KS = D / 16, DB = D / 32, T = NW * 64;
   constexpr int TILE_BYTES = BN * D * 2;
+  static_assert((TILE_BYTES & (TILE_BYTES - 1)) == 0, "buffer toggle is an XOR");
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  char* k_tiles = smem;                       // 2 buffers
-  char* v_tiles = smem + 2 * TILE_BYTES;      // 2 buffers
+  // LDS: K set 0, K set 1, V set 0, V set 1
+  constexpr int K_BASE = 0, V_BASE = 2 * TILE_BYTES;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ql = lane & 31;
+  const bool group_b = wave >= NW / 2;
   const int qblk = (int)gridDim.x - 1 - (int)blockIdx.x;   // heaviest (latest) query block first
   const int h = blockIdx.y, b = blockIdx.z, hk = h / a.group;
   const int m0 = qblk * BM, wrow0 = m0 + wave * 32;
@@ -29,13 +138,19 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
   const int myrow_c = myrow < a.s_q ? myrow : a.s_q - 1;
   const int64_t qpos = a.q_offset + myrow;
 
-  // Q as B operand: column = my query, k-slots = head_dim 16*ks + 8g ..
-  bf16x8 qreg[KS];
+  FwdState<D, BN> st;
   {
+    // Q as B operand: column = my query, k-slots = head_dim 16*ks + 8g ..
     const bf16_t* qp = a.q + (int64_t)b * a.q_stride_b + (int64_t)myrow_c * a.q_stride_s + (int64_t)h * a.q_stride_h;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks + 8 * g);
+    for (int ks = 0; ks < KS; ++ks) st.qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks + 8 * g);
   }
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) st.o[db][i] = 0.f;
+  st.m_run = -INFINITY;    // running max of score * c (log2 domain)
+  st.l_run = 0.f;          // this lane's share of the running row sum
 
   // keys this workgroup walks: [lo, hi)
   const int64_t lo = a.kv_begin;
@@ -46,116 +161,115 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
     hi = hi < lim ? hi : lim;
   }
   const int nt = hi > lo ? (int)((hi - lo + BN - 1) / BN) : 0;
-
-  const bf16_t* kbase = a.k + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
-  const bf16_t* vbase = a.v + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
-
-  f32x16 o[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
-  float m_run = -INFINITY;   // running max of score * c  (log2 domain)
-  float l_run = 0.f;         // this lane's share of the running row sum
   const float c = a.scale_log2e;
 
-  TileStage<D, BN, T> ks_stage, vs_stage;
   if (nt > 0) {
-    ks_stage.issue(kbase, a.kv_stride_s, lo, hi - 1, tid);
-    vs_stage.issue(vbase, a.kv_stride_s, lo, hi - 1, tid);
-    ks_stage.commit(k_tiles, tid);
-    vs_stage.commit(v_tiles, tid);
-  }
-  __syncthreads();
-
-  for (int t = 0; t < nt; ++t) {
-    const int64_t key0 = lo + (int64_t)t * BN;
-    const char* kt = k_tiles + (t & 1) * TILE_BYTES;
-    const char* vt = v_tiles + (t & 1) * TILE_BYTES;
-    const bool more = (t + 1 < nt);
-    if (more) {
-      ks_stage.issue(kbase, a.kv_stride_s, key0 + BN, hi - 1, tid);
-      vs_stage.issue(vbase, a.kv_stride_s, key0 + BN, hi - 1, tid);
-    }
-
-    // whole tile above this wave's causal frontier -> nothing visible
-    const bool skip = a.causal && key0 > a.q_offset + wrow0 + 31;
-    if (!skip) {
-      f32x16 s[KB];
-#pragma unroll
-      for (int kb = 0; kb < KB; ++kb) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          bf16x8 ka = lds_read_rowpacked<D>(kt, kb * 32 + ql, ks, g);
-          s[kb] = mfma32(ka, qreg[ks], s[kb]);
-        }
-      }
+    const bf16_t* kbase = a.k + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
+    const bf16_t* vbase = a.v + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
+    TileStage<D, BN, T> k_stage, v_stage;
+    RpOffsets<D> lo_k;
+    TrOffsets<D> lo_v;
+    // tile index -> first key; tiles past the end re-read the last rows (never used)
+    auto key0_of = [&](int t) { return lo + (int64_t)t * BN; };
+    // pair t = (V(t), K(t+1)) lives in set t & 1
+    auto issue_pair = [&](int t) {
+      v_stage.issue(vbase, a.kv_stride_s, key0_of(t), hi - 1, tid);
+      k_stage.issue(kbase, a.kv_stride_s, key0_of(t + 1), hi - 1, tid);
+    };
+    auto store_pair = [&](int t) {
+      v_stage.commit(smem + V_BASE + (t & 1) * TILE_BYTES, tid);
+      k_stage.commit(smem + K_BASE + (t & 1) * TILE_BYTES, tid);
+    };
+    auto softmax_tile = [&](int t) {
+      const int64_t key0 = key0_of(t);
       const bool need_mask = (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
-      if (need_mask) {
-        // last visible key of this lane's query, relative to the tile (may be < 0 or >= BN)
-        int64_t kmax = a.kv_end - 1;
-        if (a.causal && qpos < kmax) kmax = qpos;
-        kmax -= key0;
-        const int kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int key_rel = kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-            s[kb][i] = key_rel <= kmax_rel ? s[kb][i] : -INFINITY;
-          }
-      }
-      float mx = -INFINITY;
-#pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
-      mx = xhalf_max(mx);
-      const float m_new = fmaxf(m_run, mx * c);
-      const float m_eff = (m_new == -INFINITY) ? 0.f : m_new;
-      const float alpha = exp2_fast(m_run - m_eff);     // m_run = -inf -> 0
-      m_run = m_new;
-      l_run *= alpha;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-#pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float p = exp2_fast(__builtin_fmaf(s[kb][i], c, -m_eff));
-          s[kb][i] = p;
-          l_run += p;
-        }
-#pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          const bf16x8 pb = pack8(s[kb], 8 * half);
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            bf16x8 va = lds_read_transposed<D>(vt, kb * 32 + 16 * half, db, lane);
-            o[db] = mfma32(va, pb, o[db]);
-          }
-        }
-    }
-    if (more) {
-      ks_stage.commit(k_tiles + ((t + 1) & 1) * TILE_BYTES, tid);
-      vs_stage.commit(v_tiles + ((t + 1) & 1) * TILE_BYTES, tid);
-    }
+      int64_t kmax = a.kv_end - 1;
+      if (a.causal && qpos < kmax) kmax = qpos;
+      kmax -= key0;
+      const int kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
+      fwd_softmax<D, BN>(st, c, need_mask, kmax_rel, g);
+    };
+
+    // prologue: K(0) into K set 1 (the set "pair -1" would use)
+    k_stage.issue(kbase, a.kv_stride_s, key0_of(0), hi - 1, tid);
+    k_stage.commit(smem + K_BASE + TILE_BYTES, tid);
+    lo_k.init(lane, K_BASE + TILE_BYTES);   // S(t) reads K(t) from set (t-1)&1: starts at set 1
+    lo_v.init(lane, V_BASE);                // PV(t) reads V(t) from set t&1: starts at set 0
     __syncthreads();
+
+    if (!group_b) {
+      // phase 0
+      issue_pair(0);
+      fwd_scores<D, BN>(smem, lo_k, st);
+      lo_k.add(-TILE_BYTES);                // set 0 next
+      phase_end();
+#ifdef SLIMPIPE_TRACE
+      long long tr_v = 0, tr_st = 0, tr_b1 = 0, tr_is = 0, tr_m = 0, tr_b2 = 0, tr_t0 = clock64(), tr_w0 = wall_clock64(), tr_last = clock64();
+#define TR_MARK(var) { long long _n = clock64(); var += _n - tr_last; tr_last = _n; }
+#else
+#define TR_MARK(var)
+#endif
+      for (int t = 0; t < nt; ++t) {
+        // phase 2t+1: vector phase
+        softmax_tile(t);
+        TR_MARK(tr_v)
+        store_pair(t);
+        TR_MARK(tr_st)
+        phase_end();
+        TR_MARK(tr_b1)
+        // phase 2t+2: matrix phase
+        if (t + 1 < nt) issue_pair(t + 1);
+        TR_MARK(tr_is)
+        fwd_pv<D, BN>(smem, lo_v, st);
+        if (t + 1 < nt) fwd_scores<D, BN>(smem, lo_k, st);
+        const int d = (t & 1) ? -TILE_BYTES : TILE_BYTES;
+        lo_k.add(d);
+        lo_v.add(d);
+        TR_MARK(tr_m)
+        phase_end();
+        TR_MARK(tr_b2)
+      }
+#ifdef SLIMPIPE_TRACE
+      if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {
+        long long* dbg = reinterpret_cast<long long*>(a.lse + (int64_t)a.n_q_heads * a.s_q);   // caller over-allocates lse
+        dbg[0] = tr_v; dbg[1] = tr_st; dbg[2] = tr_b1; dbg[3] = tr_is; dbg[4] = tr_m; dbg[5] = tr_b2;
+        dbg[6] = clock64() - tr_t0; dbg[7] = wall_clock64() - tr_w0; dbg[8] = nt;
+      }
+#endif
+      phase_end();                      // group B's last matrix phase
+    } else {
+      // phase 0: nothing to compute yet
+      issue_pair(0);
+      phase_end();
+      // phase 1
+      fwd_scores<D, BN>(smem, lo_k, st);
+      lo_k.add(-TILE_BYTES);
+      store_pair(0);
+      phase_end();
+      for (int t = 0; t < nt; ++t) {
+        // phase 2t+2: vector phase
+        if (t + 1 < nt) issue_pair(t + 1);
+        softmax_tile(t);
+        phase_end();
+        // phase 2t+3: matrix phase
+        fwd_pv<D, BN>(smem, lo_v, st);
+        if (t + 1 < nt) fwd_scores<D, BN>(smem, lo_k, st);
+        const int d = (t & 1) ? -TILE_BYTES : TILE_BYTES;
+        lo_k.add(d);
+        lo_v.add(d);
+        if (t + 1 < nt) store_pair(t + 1);
+        phase_end();
+      }
+    }
   }
 
   // epilogue
-  const float l_tot = xhalf_sum(l_run);
+  const float l_tot = xhalf_sum(st.l_run);
   const bool has = l_tot > 0.f;
   const float inv = has ? 1.0f / l_tot : 0.f;
   if (myrow < a.s_q) {
     if (g == 0) {
-      const float lse = has ? (m_run + __builtin_log2f(l_tot)) * kLn2 : -INFINITY;
+      const float lse = has ? (st.m_run + __builtin_log2f(l_tot)) * kLn2 : -INFINITY;
       a.lse[((int64_t)b * a.n_q_heads + h) * a.s_q + myrow] = lse;
     }
     const int64_t obase = (int64_t)b * a.o_stride_b + (int64_t)myrow * a.o_stride_s + (int64_t)h * a.o_stride_h;
@@ -164,7 +278,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
         const int d = 32 * db + 8 * i4 + 4 * g;
-        f32x4 v4 = {o[db][4 * i4] * inv, o[db][4 * i4 + 1] * inv, o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv};
+        f32x4 v4 = {st.o[db][4 * i4] * inv, st.o[db][4 * i4 + 1] * inv, st.o[db][4 * i4 + 2] * inv,
+                    st.o[db][4 * i4 + 3] * inv};
         if (a.out_f32) {
           *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.out) + obase + d) = v4;
         } else {
