@@ -1,0 +1,99 @@
+"""CPU-only checks of the boundary: the shared library loads without a GPU, exports every function
+the header declares, and its host-side validation returns the documented codes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def sp():
+    import paper_2504_14519_amd as sp_
+    return sp_
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "slimpipe_attn.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(slimpipe_attn_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol(sp):
+    names = declared_functions()
+    assert {"slimpipe_attn_fwd", "slimpipe_attn_bwd", "slimpipe_attn_merge", "slimpipe_attn_finalize_bf16",
+            "slimpipe_attn_workspace_bytes", "slimpipe_attn_validate", "slimpipe_attn_strerror"} <= set(names)
+    L = ctypes.CDLL(sp.library_path())
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def good_params(sp):
+    p = sp.AttnParams()
+    p.batch, p.s_q, p.n_q_heads, p.n_kv_heads, p.head_dim, p.causal = 1, 512, 8, 1, 128, 1
+    p.kv_capacity, p.q_offset, p.kv_begin, p.kv_end = 4096, 1024, 0, 1536
+    p.scale, p.out_dtype = 0.088, sp.BF16
+    p.q_stride_b, p.q_stride_s, p.q_stride_h = 512 * 8 * 128, 8 * 128, 128
+    p.kv_stride_b, p.kv_stride_s, p.kv_stride_h = 4096 * 128, 128, 128
+    p.o_stride_b, p.o_stride_s, p.o_stride_h = 512 * 8 * 128, 8 * 128, 128
+    p.do_stride_b, p.do_stride_s, p.do_stride_h = 512 * 8 * 128, 8 * 128, 128
+    return p
+
+
+def test_validation_codes(sp):
+    assert sp.slimpipe_attn_validate(good_params(sp), True) == 0
+    cases = [
+        (dict(n_kv_heads=3), -2), (dict(head_dim=96), -2), (dict(s_q=0), -2), (dict(scale=0.0), -2),
+        (dict(scale=float("nan")), -2), (dict(causal=2), -2), (dict(out_dtype=5), -2),
+        (dict(kv_begin=2000, kv_end=1000), -3), (dict(kv_end=5000), -3), (dict(q_offset=-1), -3), (dict(kv_begin=-4), -3),
+        (dict(q_stride_s=1023), -4), (dict(kv_stride_h=0), -4), (dict(o_stride_h=64), -4), (dict(do_stride_s=12), -4),
+    ]
+    for change, code in cases:
+        p = good_params(sp)
+        for k, v in change.items():
+            setattr(p, k, v)
+        assert sp.slimpipe_attn_validate(p, True) == code, (change, code)
+    # d_out strides only matter to the backward
+    p = good_params(sp)
+    p.do_stride_s = 12
+    assert sp.slimpipe_attn_validate(p, False) == 0
+    # empty range is legal
+    p = good_params(sp)
+    p.kv_begin = p.kv_end = 700
+    assert sp.slimpipe_attn_validate(p, True) == 0
+    assert sp.lib.slimpipe_attn_validate(None, 0) == -1
+
+
+def test_workspace_bytes_and_null_pointer_errors(sp):
+    p = good_params(sp)
+    assert sp.slimpipe_attn_workspace_bytes(p, False) == 0
+    n = sp.slimpipe_attn_workspace_bytes(p, True)
+    assert n >= 2 * 4 * 8 * 512 and n % 256 == 0
+    # NULL data pointers are refused before anything touches the device
+    rc = sp.lib.slimpipe_attn_fwd(ctypes.byref(p), None, None, None, None, None, None, 0, None)
+    assert rc == -1
+    rc = sp.lib.slimpipe_attn_finalize_bf16(None, None, 16, None)
+    assert rc == -1
+    assert "workspace" in sp.slimpipe_attn_strerror(-6)
+    assert sp.slimpipe_attn_strerror(12345) == "unknown slimpipe status"
+
+
+def test_equal_flop_cuts():
+    from paper_2504_14519_amd.planner import equal_flop_cuts, visible_pairs_upto
+    s, i = 4096, 20
+    q_off = i * s
+    for parts in (2, 3, 5):
+        cuts = equal_flop_cuts(s, q_off, parts)
+        assert cuts[0] == 0 and cuts[-1] == q_off + s and len(cuts) == parts + 1
+        assert all(c % 128 == 0 for c in cuts) and cuts == sorted(cuts)
+        total = visible_pairs_upto(s, q_off, q_off + s)
+        work = [visible_pairs_upto(s, q_off, b) - visible_pairs_upto(s, q_off, a) for a, b in zip(cuts[:-1], cuts[1:])]
+        assert sum(work) == total
+        assert max(work) - min(work) <= 2 * 128 * s          # within an alignment step of equal
+    # brute-force count of the closed form
+    s, q_off = 7, 10
+    for e in range(0, 20):
+        brute = sum(1 for r in range(s) for j in range(e) if j <= q_off + r)
+        assert visible_pairs_upto(s, q_off, e) == brute
