@@ -132,7 +132,7 @@ def main():
     achieved = dom_flops_total / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
     roofline = {
         "bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-        "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+        "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": stored_traffic(c["name"], dom),
         "launches": int(dom_n), "avg_launch_ms": round(dom_ms / max(1, dom_n), 4),
         "flops_per_launch_avg": dom_flops_total / max(1, dom_n),
         "kernel_ms_per_step": {kk: round(prof[kk][0] / args.steps, 3) for kk in prof},
@@ -155,6 +155,20 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg_id, c, s, scale)
     print(json.dumps(out), flush=True)
+
+
+def stored_traffic(workload, kernel):
+    """HBM-side bytes per launch of `kernel` from the committed rocprofv3 counter summary (FETCH_SIZE and
+    WRITE_SIZE runs scaled by a plain streaming kernel), or None if there is none for this workload."""
+    path = os.path.join(ROOT, "profiles", "bench_%s_counters.txt" % workload)
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and f[1] == kernel:
+                return float(f[2])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(cfg_id, c, s, scale):
