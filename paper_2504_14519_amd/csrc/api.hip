@@ -93,6 +93,10 @@ int slimpipe_attn_validate(const slimpipe_attn_params* p, int is_bwd) {
     return SLIMPIPE_EINVAL_STRIDE;
   if (p->q_stride_h < p->head_dim || p->kv_stride_h < p->head_dim || p->o_stride_h < p->head_dim)
     return SLIMPIPE_EINVAL_STRIDE;
+  /* row strides enter 32-bit byte offsets inside a tile */
+  if (p->q_stride_s >= (1 << 22) || p->kv_stride_s >= (1 << 22) || p->o_stride_s >= (1 << 22) ||
+      (is_bwd && p->do_stride_s >= (1 << 22)))
+    return SLIMPIPE_EINVAL_STRIDE;
   return SLIMPIPE_OK;
 }
 
@@ -123,7 +127,7 @@ int slimpipe_attn_fwd(const slimpipe_attn_params* p, const void* q_slice, const 
   a.lse = lse;
   a.s_q = p->s_q; a.n_q_heads = p->n_q_heads; a.group = p->n_q_heads / p->n_kv_heads;
   a.causal = p->causal; a.out_f32 = (p->out_dtype == SLIMPIPE_F32);
-  a.q_offset = p->q_offset; a.kv_begin = p->kv_begin; a.kv_end = p->kv_end;
+  a.q_offset = p->q_offset; a.kv_begin = p->kv_begin; a.kv_end = p->kv_end; a.kv_capacity = p->kv_capacity;
   a.scale_log2e = p->scale * 1.4426950408889634f;
   a.q_stride_b = p->q_stride_b; a.q_stride_s = p->q_stride_s; a.q_stride_h = p->q_stride_h;
   a.kv_stride_b = p->kv_stride_b; a.kv_stride_s = p->kv_stride_s; a.kv_stride_h = p->kv_stride_h;
@@ -163,7 +167,7 @@ int slimpipe_attn_bwd(const slimpipe_attn_params* p, const void* q_slice, const 
   a.group = p->n_q_heads / p->n_kv_heads; a.causal = p->causal;
   a.dq_f32 = (dq_dtype == SLIMPIPE_F32); a.dq_accumulate = dq_accumulate ? 1 : 0;
   a.dkv_accumulate = dkv_accumulate ? 1 : 0;
-  a.q_offset = p->q_offset; a.kv_begin = p->kv_begin; a.kv_end = p->kv_end;
+  a.q_offset = p->q_offset; a.kv_begin = p->kv_begin; a.kv_end = p->kv_end; a.kv_capacity = p->kv_capacity;
   a.scale = p->scale; a.scale_log2e = p->scale * 1.4426950408889634f;
   a.q_stride_b = p->q_stride_b; a.q_stride_s = p->q_stride_s; a.q_stride_h = p->q_stride_h;
   a.kv_stride_b = p->kv_stride_b; a.kv_stride_s = p->kv_stride_s; a.kv_stride_h = p->kv_stride_h;

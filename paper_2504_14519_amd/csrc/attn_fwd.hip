@@ -9,25 +9,17 @@
 //   O^T += V^T P^T     A = V through the transposed LDS read, B = P straight from the C registers
 // Scores and probabilities never leave registers.
 //
-// Schedule.  A wave alternates a matrix phase  M(t): O += P(t) V(t), S(t+1) = K(t+1) Q^T  with a
-// vector phase  V(t): P(t) = softmax(S(t)).  A SIMD hosts two waves of the workgroup; waves 0-3
-// (group A) and waves 4-7 (group B) run the same sequence one phase apart, with one workgroup
-// barrier per phase, so that on every SIMD one wave feeds the matrix pipe while the other runs the
-// softmax.  The pair (V(t), K(t+1)) that M(t) needs lives in one of two LDS buffer sets; the pair
-// after it is fetched to registers at the start of an even phase and written to the other set at
-// the end of the following odd phase.
+// Schedule.  All 8 waves walk the tiles in step (S, softmax, PV, one barrier per tile).  A SIMD hosts
+// two of them, so in the S and PV parts the LDS latency of one wave is covered by the MFMAs of the
+// other.  K(t+1) and V(t+1) are copied global->LDS asynchronously into the other buffer set while
+// tile t is computed; the copy instructions are spread over the tile because the L1 path moves
+// 64 bytes per clock for the whole CU and a wave stalls at issue while it is busy.
+#include <stdlib.h>
+
 #include "kernels.hpp"
 #include "tile_common.hpp"
 
 namespace slimpipe {
-
-// End of a phase: nothing may be scheduled across it (the point of the two groups is that the
-// vector work of one wave runs while the OTHER wave of the SIMD has the matrix pipe).
-SP_DEV void phase_end() {
-  __builtin_amdgcn_sched_barrier(0);
-  __syncthreads();
-  __builtin_amdgcn_sched_barrier(0);
-}
 
 template <int D, int BN>
 struct FwdState {
@@ -39,39 +31,66 @@ struct FwdState {
   float m_run, l_run;
 };
 
+// scheduling-group classes of __builtin_amdgcn_sched_group_barrier
+#define SP_SG_MFMA 0x8
+#define SP_SG_DSRD 0x100
+
+// Ask the scheduler for "LDS reads LOOK MFMAs ahead of their use": a block of reads first, then one
+// MFMA followed by the reads of the MFMA LOOK places later.  An LDS read takes several MFMA times to
+// come back and a wave issues in order, so reads placed right before their MFMA stall it.
+template <int N_MFMA, int READS_PER_MFMA, int LOOK>
+SP_DEV void sched_reads_ahead() {
+  __builtin_amdgcn_sched_group_barrier(SP_SG_DSRD, LOOK * READS_PER_MFMA, 0);
+#pragma unroll
+  for (int i = 0; i < N_MFMA - LOOK; ++i) {
+    __builtin_amdgcn_sched_group_barrier(SP_SG_MFMA, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(SP_SG_DSRD, READS_PER_MFMA, 0);
+  }
+  __builtin_amdgcn_sched_group_barrier(SP_SG_MFMA, LOOK, 0);
+}
+
 // S(t)^T = K(t) Q^T for this wave's 32 queries.
 template <int D, int BN>
 SP_DEV void fwd_scores(const char* smem, const RpOffsets<D>& lo_k, FwdState<D, BN>& st) {
+  constexpr int KB = BN / 32, KS = D / 16;
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int kb = 0; kb < BN / 32; ++kb) {
+  for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
     for (int i = 0; i < 16; ++i) st.s[kb][i] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) {
+  for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {          // the KB accumulator chains interleaved
       const bf16x8 ka = lds_rp<D>(smem, lo_k, ks, kb * 32 * D * 2);
       st.s[kb] = mfma32(ka, st.qreg[ks], st.s[kb]);
     }
-  }
+  sched_reads_ahead<KB * KS, 1, 4>();
+  __builtin_amdgcn_sched_barrier(0);
 }
 
 // O^T += V(t)^T P(t)^T.
 template <int D, int BN>
 SP_DEV void fwd_pv(const char* smem, const TrOffsets<D>& lo_v, FwdState<D, BN>& st) {
+  constexpr int KB = BN / 32, DB = D / 32;
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int kb = 0; kb < BN / 32; ++kb)
+  for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
     for (int half = 0; half < 2; ++half)
 #pragma unroll
-      for (int db = 0; db < D / 32; ++db) {
+      for (int db = 0; db < DB; ++db) {
         const bf16x8 va = lds_tr<D>(smem, lo_v, db, (kb * 32 + 16 * half) * D * 2);
         st.o[db] = mfma32(va, st.p[kb][half], st.o[db]);
       }
+  sched_reads_ahead<KB * 2 * DB, 2, 4>();
+  __builtin_amdgcn_sched_barrier(0);
 }
 
 // P(t) = online softmax of S(t); rescales O and the running sum when a row maximum moves.
 // kmax_rel: last visible key of this lane's query relative to the tile (>= BN: no mask needed).
-template <int D, int BN>
-SP_DEV void fwd_softmax(FwdState<D, BN>& st, float c, bool need_mask, int kmax_rel, int g) {
+template <int D, int BN, bool PIN, class H>
+SP_DEV void fwd_softmax(FwdState<D, BN>& st, float c, bool need_mask, int kmax_rel, int g, H&& hook) {
   constexpr int KB = BN / 32, DB = D / 32;
   if (need_mask) {
 #pragma unroll
@@ -82,12 +101,14 @@ SP_DEV void fwd_softmax(FwdState<D, BN>& st, float c, bool need_mask, int kmax_r
         st.s[kb][i] = key_rel <= kmax_rel ? st.s[kb][i] : -INFINITY;
       }
   }
+  hook(0);
   float mx = -INFINITY;
 #pragma unroll
   for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
     for (int i = 0; i < 16; ++i) mx = fmaxf(mx, st.s[kb][i]);
   mx = xhalf_max(mx);
+  hook(1);
   const float m_new = fmaxf(st.m_run, mx * c);
   const float m_eff = (m_new == -INFINITY) ? 0.f : m_new;
   // rescale only when some row of the wave moved its maximum (rare once a few tiles are in)
@@ -103,6 +124,7 @@ SP_DEV void fwd_softmax(FwdState<D, BN>& st, float c, bool need_mask, int kmax_r
   float l_add = 0.f;
 #pragma unroll
   for (int kb = 0; kb < KB; ++kb) {
+    hook(2 + kb);
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const float p = exp2_fast(__builtin_fmaf(st.s[kb][i], c, -m_eff));
@@ -111,17 +133,45 @@ SP_DEV void fwd_softmax(FwdState<D, BN>& st, float c, bool need_mask, int kmax_r
     }
     st.p[kb][0] = pack8(st.s[kb], 0);
     st.p[kb][1] = pack8(st.s[kb], 8);
-    // pin the values here: without a use the optimiser sinks this arithmetic past the phase barrier
-    // into the matrix phase of the same wave
-    asm volatile("" : "+v"(st.p[kb][0]), "+v"(st.p[kb][1]));
+    // PIN: without a use here the optimiser sinks this arithmetic past the phase barrier that follows
+    if (PIN) asm volatile("" : "+v"(st.p[kb][0]), "+v"(st.p[kb][1]));
   }
   st.l_run += l_add;
-  asm volatile("" : "+v"(st.l_run));
+  if (PIN) asm volatile("" : "+v"(st.l_run));
+}
+
+// out = O / l, lse = (m + log2 l) ln 2; rows that saw no key: out = 0, lse = -inf.
+template <int D, int BN>
+SP_DEV void fwd_epilogue(const FwdArgs& a, FwdState<D, BN>& st, int myrow, int h, int b, int g) {
+  constexpr int DB = D / 32;
+  const float l_tot = xhalf_sum(st.l_run);
+  const bool has = l_tot > 0.f;
+  const float inv = has ? 1.0f / l_tot : 0.f;
+  if (myrow < a.s_q) {
+    if (g == 0) {
+      const float lse = has ? (st.m_run + __builtin_log2f(l_tot)) * kLn2 : -INFINITY;
+      a.lse[((int64_t)b * a.n_q_heads + h) * a.s_q + myrow] = lse;
+    }
+    const int64_t obase = (int64_t)b * a.o_stride_b + (int64_t)myrow * a.o_stride_s + (int64_t)h * a.o_stride_h;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const int d = 32 * db + 8 * i4 + 4 * g;
+        f32x4 v4 = {st.o[db][4 * i4] * inv, st.o[db][4 * i4 + 1] * inv, st.o[db][4 * i4 + 2] * inv,
+                    st.o[db][4 * i4 + 3] * inv};
+        if (a.out_f32) {
+          *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.out) + obase + d) = v4;
+        } else {
+          bf16x4 h4 = __builtin_convertvector(v4, bf16x4);
+          *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16_t*>(a.out) + obase + d) = h4;
+        }
+      }
+  }
 }
 
 template <int D, int NW, int BN>
 __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
-  static_assert(NW == 8, "two groups of four waves");
   constexpr int BM = NW * 32, KS = D / 16, DB = D / 32, T = NW * 64;
   constexpr int TILE_BYTES = BN * D * 2;
   static_assert((TILE_BYTES & (TILE_BYTES - 1)) == 0, "buffer toggle is an XOR");
@@ -130,7 +180,6 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
   constexpr int K_BASE = 0, V_BASE = 2 * TILE_BYTES;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ql = lane & 31;
-  const bool group_b = wave >= NW / 2;
   const int qblk = (int)gridDim.x - 1 - (int)blockIdx.x;   // heaviest (latest) query block first
   const int h = blockIdx.y, b = blockIdx.z, hk = h / a.group;
   const int m0 = qblk * BM, wrow0 = m0 + wave * 32;
@@ -166,90 +215,217 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
   if (nt > 0) {
     const bf16_t* kbase = a.k + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
     const bf16_t* vbase = a.v + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
-    TileStage<D, BN, T> k_stage, v_stage;
     RpOffsets<D> lo_k;
     TrOffsets<D> lo_v;
-    // tile index -> first key; tiles past the end re-read the last rows (never used)
+    lo_k.init(lane, K_BASE);
+    lo_v.init(lane, V_BASE);
     auto key0_of = [&](int t) { return lo + (int64_t)t * BN; };
-    // pair t = (V(t), K(t+1)) lives in set t & 1
-    auto issue_pair = [&](int t) {
-      v_stage.issue(vbase, a.kv_stride_s, key0_of(t), hi - 1, tid);
-      k_stage.issue(kbase, a.kv_stride_s, key0_of(t + 1), hi - 1, tid);
+    constexpr int PASSES = BN * (D / 8) / T;             // copy instructions per tile and wave
+    TileDma<D, BN, T> dma;
+    dma.init(a.kv_stride_s, tid);
+    // quarter `part` of the copies of K(t), V(t) into set t & 1 (parts 0,1: K; 2,3: V)
+    auto issue_part = [&](int t, int part) {
+      if (t >= nt) return;
+      const bf16_t* base = part < 2 ? kbase : vbase;
+      char* dst = smem + (part < 2 ? K_BASE : V_BASE) + (t & 1) * TILE_BYTES;
+      const int64_t key0 = key0_of(t);
+      const bool whole = key0 + BN <= a.kv_capacity;     // every row of the tile exists in memory
+#pragma unroll
+      for (int n = 0; n < PASSES; ++n)
+        if (PASSES == 1 ? (part & 1) == 0 : (n & 1) == (part & 1)) {
+          if (whole) dma.issue(dst, base + key0 * a.kv_stride_s, tid, n);
+          else tile_load_async_pass<D, T>(dst, base, a.kv_stride_s, key0, hi - 1, tid, n);
+        }
     };
-    auto store_pair = [&](int t) {
-      v_stage.commit(smem + V_BASE + (t & 1) * TILE_BYTES, tid);
-      k_stage.commit(smem + K_BASE + (t & 1) * TILE_BYTES, tid);
+
+    for (int part = 0; part < 4; ++part) issue_part(0, part);
+    wait_async();
+    __syncthreads();
+
+#ifdef SLIMPIPE_TRACE
+    long long tr_s = 0, tr_v = 0, tr_pv = 0, tr_b = 0, tr_w = 0, tr_t0 = clock64(), tr_w0 = wall_clock64(), tr_last = clock64();
+#define TR_MARK(var) { long long _n = clock64(); var += _n - tr_last; tr_last = _n; }
+#else
+#define TR_MARK(var)
+#endif
+    for (int t = 0; t < nt; ++t) {
+      const int64_t key0 = key0_of(t);
+      // whole tile above this wave's causal frontier -> nothing visible (the wave still helps copying)
+      const bool skip = a.causal && key0 > a.q_offset + wrow0 + 31;
+      if (!skip) {
+        issue_part(t + 1, 0);
+        issue_part(t + 1, 1);
+        fwd_scores<D, BN>(smem, lo_k, st);
+        TR_MARK(tr_s)
+        const bool need_mask = (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
+        int64_t kmax = a.kv_end - 1;
+        if (a.causal && qpos < kmax) kmax = qpos;
+        kmax -= key0;
+        const int kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
+        fwd_softmax<D, BN, false>(st, c, need_mask, kmax_rel, g, [](int) {});
+        TR_MARK(tr_v)
+        issue_part(t + 1, 2);
+        issue_part(t + 1, 3);
+        fwd_pv<D, BN>(smem, lo_v, st);
+        TR_MARK(tr_pv)
+      } else {
+        for (int part = 0; part < 4; ++part) issue_part(t + 1, part);
+      }
+      const int d = (t & 1) ? -TILE_BYTES : TILE_BYTES;
+      lo_k.add(d);
+      lo_v.add(d);
+      wait_async();
+      TR_MARK(tr_w)
+      __syncthreads();
+      TR_MARK(tr_b)
+    }
+#ifdef SLIMPIPE_TRACE
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {
+      long long* dbg = reinterpret_cast<long long*>(a.lse + (int64_t)a.n_q_heads * a.s_q);   // caller over-allocates lse
+      dbg[0] = tr_s; dbg[1] = tr_v; dbg[2] = tr_pv; dbg[3] = tr_b; dbg[4] = tr_w; dbg[5] = 0;
+      dbg[6] = clock64() - tr_t0; dbg[7] = wall_clock64() - tr_w0; dbg[8] = nt;
+    }
+#endif
+  }
+
+  fwd_epilogue<D, BN>(a, st, myrow, h, b, g);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Variant with the two wave groups one phase apart.  A wave alternates a matrix phase
+// M(t): O += P(t) V(t), S(t+1) = K(t+1) Q^T  with a vector phase  V(t): P(t) = softmax(S(t)).
+// Waves 0-3 (group A) and 4-7 (group B) run the same sequence shifted by one phase, one workgroup
+// barrier per phase, so every SIMD hosts one wave in each kind of phase.  The pair (V(t), K(t+1))
+// that M(t) needs lives in one of two LDS buffer sets; the next pair is copied asynchronously during
+// the two phases before it is needed.
+SP_DEV void phase_end() {
+  __builtin_amdgcn_sched_barrier(0);
+  __syncthreads();
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int D, int NW, int BN>
+__global__ __launch_bounds__(NW * 64) void attn_fwd_pp_kernel(const FwdArgs a) {
+  static_assert(NW == 8, "two groups of four waves");
+  constexpr int BM = NW * 32, KS = D / 16, DB = D / 32, T = NW * 64;
+  constexpr int TILE_BYTES = BN * D * 2;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  constexpr int K_BASE = 0, V_BASE = 2 * TILE_BYTES;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ql = lane & 31;
+  const bool group_b = wave >= NW / 2;
+  const int qblk = (int)gridDim.x - 1 - (int)blockIdx.x;
+  const int h = blockIdx.y, b = blockIdx.z, hk = h / a.group;
+  const int m0 = qblk * BM, wrow0 = m0 + wave * 32;
+  const int myrow = wrow0 + ql;
+  const int myrow_c = myrow < a.s_q ? myrow : a.s_q - 1;
+  const int64_t qpos = a.q_offset + myrow;
+
+  FwdState<D, BN> st;
+  {
+    const bf16_t* qp = a.q + (int64_t)b * a.q_stride_b + (int64_t)myrow_c * a.q_stride_s + (int64_t)h * a.q_stride_h;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) st.qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks + 8 * g);
+  }
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) st.o[db][i] = 0.f;
+  st.m_run = -INFINITY;
+  st.l_run = 0.f;
+
+  const int64_t lo = a.kv_begin;
+  int64_t hi = a.kv_end;
+  if (a.causal) {
+    const int last_row = (m0 + BM < a.s_q ? m0 + BM : a.s_q);
+    const int64_t lim = a.q_offset + last_row;
+    hi = hi < lim ? hi : lim;
+  }
+  const int nt = hi > lo ? (int)((hi - lo + BN - 1) / BN) : 0;
+  const float c = a.scale_log2e;
+
+  if (nt > 0) {
+    const bf16_t* kbase = a.k + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
+    const bf16_t* vbase = a.v + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
+    RpOffsets<D> lo_k;
+    TrOffsets<D> lo_v;
+    auto key0_of = [&](int t) { return lo + (int64_t)t * BN; };
+    constexpr int PASSES = BN * (D / 8) / T;
+    TileDma<D, BN, T> dma;
+    dma.init(a.kv_stride_s, tid);
+    // one tile (is_k: K(t) else V(t)) into buffer set `set`, passes with n % 2 == half
+    auto copy_half = [&](bool is_k, int t, int set, int half) {
+      if (t >= nt) return;
+      const bf16_t* base = is_k ? kbase : vbase;
+      char* dst = smem + (is_k ? K_BASE : V_BASE) + set * TILE_BYTES;
+      const int64_t key0 = key0_of(t);
+      const bool whole = key0 + BN <= a.kv_capacity;
+#pragma unroll
+      for (int n = 0; n < PASSES; ++n)
+        if (PASSES == 1 ? half == 0 : (n & 1) == half) {
+          if (whole) dma.issue(dst, base + key0 * a.kv_stride_s, tid, n);
+          else tile_load_async_pass<D, T>(dst, base, a.kv_stride_s, key0, hi - 1, tid, n);
+        }
     };
-    auto softmax_tile = [&](int t) {
+    // pair t = (V(t), K(t+1)) lives in set t & 1; quarter `part` of its copies
+    auto issue_pair_part = [&](int t, int part) {
+      if (part < 2) copy_half(false, t, t & 1, part);
+      else copy_half(true, t + 1, t & 1, part - 2);
+    };
+    auto softmax_tile = [&](int t, auto&& hook) {
       const int64_t key0 = key0_of(t);
       const bool need_mask = (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
       int64_t kmax = a.kv_end - 1;
       if (a.causal && qpos < kmax) kmax = qpos;
       kmax -= key0;
       const int kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
-      fwd_softmax<D, BN>(st, c, need_mask, kmax_rel, g);
+      fwd_softmax<D, BN, true>(st, c, need_mask, kmax_rel, g, hook);
     };
 
     // prologue: K(0) into K set 1 (the set "pair -1" would use)
-    k_stage.issue(kbase, a.kv_stride_s, key0_of(0), hi - 1, tid);
-    k_stage.commit(smem + K_BASE + TILE_BYTES, tid);
+    copy_half(true, 0, 1, 0);
+    copy_half(true, 0, 1, 1);
+    wait_async();
     lo_k.init(lane, K_BASE + TILE_BYTES);   // S(t) reads K(t) from set (t-1)&1: starts at set 1
     lo_v.init(lane, V_BASE);                // PV(t) reads V(t) from set t&1: starts at set 0
     __syncthreads();
 
     if (!group_b) {
       // phase 0
-      issue_pair(0);
+      for (int part = 0; part < 4; ++part) issue_pair_part(0, part);
       fwd_scores<D, BN>(smem, lo_k, st);
-      lo_k.add(-TILE_BYTES);                // set 0 next
+      lo_k.add(-TILE_BYTES);
       phase_end();
-#ifdef SLIMPIPE_TRACE
-      long long tr_v = 0, tr_st = 0, tr_b1 = 0, tr_is = 0, tr_m = 0, tr_b2 = 0, tr_t0 = clock64(), tr_w0 = wall_clock64(), tr_last = clock64();
-#define TR_MARK(var) { long long _n = clock64(); var += _n - tr_last; tr_last = _n; }
-#else
-#define TR_MARK(var)
-#endif
       for (int t = 0; t < nt; ++t) {
-        // phase 2t+1: vector phase
-        softmax_tile(t);
-        TR_MARK(tr_v)
-        store_pair(t);
-        TR_MARK(tr_st)
+        // phase 2t+1: vector phase; pair t must have landed when it ends
+        softmax_tile(t, [](int) {});
+        wait_async();
         phase_end();
-        TR_MARK(tr_b1)
-        // phase 2t+2: matrix phase
-        if (t + 1 < nt) issue_pair(t + 1);
-        TR_MARK(tr_is)
+        // phase 2t+2: matrix phase; the copies of pair t+1 ride along
+        issue_pair_part(t + 1, 0);
+        issue_pair_part(t + 1, 1);
         fwd_pv<D, BN>(smem, lo_v, st);
+        issue_pair_part(t + 1, 2);
+        issue_pair_part(t + 1, 3);
         if (t + 1 < nt) fwd_scores<D, BN>(smem, lo_k, st);
         const int d = (t & 1) ? -TILE_BYTES : TILE_BYTES;
         lo_k.add(d);
         lo_v.add(d);
-        TR_MARK(tr_m)
         phase_end();
-        TR_MARK(tr_b2)
       }
-#ifdef SLIMPIPE_TRACE
-      if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {
-        long long* dbg = reinterpret_cast<long long*>(a.lse + (int64_t)a.n_q_heads * a.s_q);   // caller over-allocates lse
-        dbg[0] = tr_v; dbg[1] = tr_st; dbg[2] = tr_b1; dbg[3] = tr_is; dbg[4] = tr_m; dbg[5] = tr_b2;
-        dbg[6] = clock64() - tr_t0; dbg[7] = wall_clock64() - tr_w0; dbg[8] = nt;
-      }
-#endif
-      phase_end();                      // group B's last matrix phase
+      phase_end();                          // group B's last matrix phase
     } else {
       // phase 0: nothing to compute yet
-      issue_pair(0);
+      for (int part = 0; part < 4; ++part) issue_pair_part(0, part);
       phase_end();
       // phase 1
       fwd_scores<D, BN>(smem, lo_k, st);
       lo_k.add(-TILE_BYTES);
-      store_pair(0);
+      wait_async();
       phase_end();
       for (int t = 0; t < nt; ++t) {
-        // phase 2t+2: vector phase
-        if (t + 1 < nt) issue_pair(t + 1);
-        softmax_tile(t);
+        // phase 2t+2: vector phase, issuing its share of the copies of pair t+1
+        softmax_tile(t, [&](int part) { issue_pair_part(t + 1, part); });
         phase_end();
         // phase 2t+3: matrix phase
         fwd_pv<D, BN>(smem, lo_v, st);
@@ -257,58 +433,34 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
         const int d = (t & 1) ? -TILE_BYTES : TILE_BYTES;
         lo_k.add(d);
         lo_v.add(d);
-        if (t + 1 < nt) store_pair(t + 1);
+        wait_async();
         phase_end();
       }
     }
   }
-
-  // epilogue
-  const float l_tot = xhalf_sum(st.l_run);
-  const bool has = l_tot > 0.f;
-  const float inv = has ? 1.0f / l_tot : 0.f;
-  if (myrow < a.s_q) {
-    if (g == 0) {
-      const float lse = has ? (st.m_run + __builtin_log2f(l_tot)) * kLn2 : -INFINITY;
-      a.lse[((int64_t)b * a.n_q_heads + h) * a.s_q + myrow] = lse;
-    }
-    const int64_t obase = (int64_t)b * a.o_stride_b + (int64_t)myrow * a.o_stride_s + (int64_t)h * a.o_stride_h;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const int d = 32 * db + 8 * i4 + 4 * g;
-        f32x4 v4 = {st.o[db][4 * i4] * inv, st.o[db][4 * i4 + 1] * inv, st.o[db][4 * i4 + 2] * inv,
-                    st.o[db][4 * i4 + 3] * inv};
-        if (a.out_f32) {
-          *reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.out) + obase + d) = v4;
-        } else {
-          bf16x4 h4 = __builtin_convertvector(v4, bf16x4);
-          *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16_t*>(a.out) + obase + d) = h4;
-        }
-      }
-  }
+  fwd_epilogue<D, BN>(a, st, myrow, h, b, g);
 }
 
-template <int D, int NW, int BN>
+template <int D, int NW, int BN, bool PP>
 static hipError_t launch_fwd_t(const FwdArgs& a, int batch, hipStream_t st) {
   constexpr int BM = NW * 32;
   const size_t smem = (size_t)4 * BN * D * 2;
+  auto kern = PP ? &attn_fwd_pp_kernel<D, NW, BN> : &attn_fwd_kernel<D, NW, BN>;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_kernel<D, NW, BN>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   dim3 grid((a.s_q + BM - 1) / BM, a.n_q_heads, batch), block(NW * 64);
-  hipLaunchKernelGGL((attn_fwd_kernel<D, NW, BN>), grid, block, smem, st, a);
+  hipLaunchKernelGGL(kern, grid, block, smem, st, a);
   return hipGetLastError();
 }
 
 hipError_t launch_fwd(const FwdArgs& a, int batch, int head_dim, hipStream_t st) {
-  if (head_dim == 128) return launch_fwd_t<128, 8, 64>(a, batch, st);
-  return launch_fwd_t<64, 8, 64>(a, batch, st);
+  static const int pp = [] { const char* e = getenv("SLIMPIPE_FWD_PP"); return e ? atoi(e) : 1; }();
+  if (head_dim == 128) return pp ? launch_fwd_t<128, 8, 64, true>(a, batch, st) : launch_fwd_t<128, 8, 64, false>(a, batch, st);
+  return pp ? launch_fwd_t<64, 8, 64, true>(a, batch, st) : launch_fwd_t<64, 8, 64, false>(a, batch, st);
 }
 
 }  // namespace slimpipe

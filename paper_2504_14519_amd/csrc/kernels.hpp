@@ -12,7 +12,7 @@ struct FwdArgs {
   void* out;
   float* lse;
   int32_t s_q, n_q_heads, group, causal, out_f32;
-  int64_t q_offset, kv_begin, kv_end;
+  int64_t q_offset, kv_begin, kv_end, kv_capacity;
   float scale_log2e;
   int64_t q_stride_b, q_stride_s, q_stride_h;
   int64_t kv_stride_b, kv_stride_s, kv_stride_h;
@@ -33,7 +33,7 @@ struct BwdArgs {
   float* dv_acc;
   int32_t s_q, n_q_heads, n_kv_heads, group, causal;
   int32_t dq_f32, dq_accumulate, dkv_accumulate;
-  int64_t q_offset, kv_begin, kv_end;
+  int64_t q_offset, kv_begin, kv_end, kv_capacity;
   float scale, scale_log2e;
   int64_t q_stride_b, q_stride_s, q_stride_h;
   int64_t kv_stride_b, kv_stride_s, kv_stride_h;

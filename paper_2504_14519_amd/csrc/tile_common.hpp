@@ -186,10 +186,17 @@ struct TileStage {
 };
 
 // Asynchronous staging of a ROWS x D bf16 tile with global_load_lds_dwordx4: every lane hands in a
-// global address, the hardware writes the 16 bytes of lane L of a wave to (wave-uniform LDS base)
-// + 16*L.  One wave instruction therefore fills 1 KB of consecutive PHYSICAL chunks; the lane
-// picks the global chunk that the swizzle maps to its physical slot.  No staging registers;
-// completion is tracked by vmcnt (wait_async() before the barrier that publishes the tile).
+// global address, the hardware writes the 16 bytes of lane L of a wave to (M0 = wave-uniform LDS
+// base) + 16*L.  One wave instruction therefore fills 1 KB of consecutive PHYSICAL chunks; the lane
+// picks the global chunk that the swizzle maps to its physical slot.  No staging registers.
+// The instruction is issued from inline assembly on purpose: through the compiler builtin every
+// later LDS read is assumed to alias the copy and the wave is made to wait for it on the spot.
+// Here the kernel owns the ordering: the copy targets a buffer nobody reads until the issuing wave
+// has executed wait_async() and the workgroup has passed a barrier.
+SP_DEV void dma16(const void* src, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(src), "s"(lds_base) : "memory", "m0");
+}
 template <int D, int ROWS, int THREADS>
 SP_DEV void tile_load_async(char* tile, const bf16_t* base, int64_t row_stride, int64_t row0, int64_t row_last, int tid) {
   constexpr int NC = D / 8;
@@ -207,12 +214,14 @@ SP_DEV void tile_load_async(char* tile, const bf16_t* base, int64_t row_stride, 
     gr = gr < row_last ? gr : row_last;
     const bf16_t* src = base + gr * row_stride + c * 8;
     char* dst = tile + (n * THREADS + wave * 64) * 16;            // wave-uniform
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                     (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+    const unsigned lds = __builtin_amdgcn_readfirstlane(
+        (unsigned)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char*)dst));
+    dma16(src, lds);
   }
 }
 // One pass (THREADS chunks = THREADS/NC rows) of the same staging, so that a kernel can spread the
-// passes of a tile over its compute phase instead of issuing them back to back.
+// passes of a tile over a phase: the L1 path moves 64 bytes per clock for the whole CU and a wave
+// stalls at issue while it is busy.
 template <int D, int THREADS>
 SP_DEV void tile_load_async_pass(char* tile, const bf16_t* base, int64_t row_stride, int64_t row0, int64_t row_last,
                                  int tid, int n) {
@@ -227,9 +236,39 @@ SP_DEV void tile_load_async_pass(char* tile, const bf16_t* base, int64_t row_str
   gr = gr < row_last ? gr : row_last;
   const bf16_t* src = base + gr * row_stride + c * 8;
   char* dst = tile + (n * THREADS + wave * 64) * 16;            // wave-uniform
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                   (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+  const unsigned lds = __builtin_amdgcn_readfirstlane(
+      (unsigned)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char*)dst));
+  dma16(src, lds);
 }
+// Loop-invariant part of that staging: the byte offset of this lane's chunk of pass n relative to
+// the first row of a tile, and the wave's LDS slot.  A tile copy is then "uniform base + lane offset"
+// (scalar base register + 32-bit vector offset), with no per-tile address arithmetic on the VALU.
+// Only valid when all ROWS rows of the tile exist in memory (callers take the clamped path otherwise).
+template <int D, int ROWS, int THREADS>
+struct TileDma {
+  static constexpr int NC = D / 8, PASSES = ROWS * NC / THREADS;
+  uint32_t goff[PASSES];
+  SP_DEV void init(int64_t row_stride, int tid) {
+#pragma unroll
+    for (int n = 0; n < PASSES; ++n) {
+      const int id = tid + n * THREADS;
+      const int r = id / NC, p = id % NC;
+      int c;
+      if constexpr (D == 128) c = ((((p >> 2) ^ r) & 3) << 2) | (((p & 3) ^ (r >> 2)) & 3);
+      else c = (p ^ r) & (NC - 1);
+      goff[n] = (uint32_t)((r * row_stride + c * 8) * 2);
+    }
+  }
+  // pass n of the tile whose first row starts at `tile_base` (uniform) into LDS `tile`
+  SP_DEV void issue(char* tile, const bf16_t* tile_base, int tid, int n) const {
+    const int wave = tid >> 6;
+    char* dst = tile + (n * THREADS + wave * 64) * 16;            // wave-uniform
+    const unsigned lds = __builtin_amdgcn_readfirstlane(
+        (unsigned)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char*)dst));
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :: "v"(goff[n]), "s"(tile_base), "s"(lds) : "memory", "m0");
+  }
+};
 
 // vmcnt(0), other counters untouched (gfx9 encoding: vmcnt[3:0]|[15:14], expcnt[6:4], lgkmcnt[11:8]).
 SP_DEV void wait_async() { __builtin_amdgcn_s_waitcnt(0x0F70); }
