@@ -65,7 +65,7 @@ SP_DEV void fwd_scores(const char* smem, const RpOffsets<D>& lo_k, FwdState<D, B
       const bf16x8 ka = lds_rp<D>(smem, lo_k, ks, kb * 32 * D * 2);
       st.s[kb] = mfma32(ka, st.qreg[ks], st.s[kb]);
     }
-  sched_reads_ahead<KB * KS, 1, 4>();
+  sched_reads_ahead<KB * KS, 1, 2>();
   __builtin_amdgcn_sched_barrier(0);
 }
 
@@ -83,7 +83,7 @@ SP_DEV void fwd_pv(const char* smem, const TrOffsets<D>& lo_v, FwdState<D, BN>& 
         const bf16x8 va = lds_tr<D>(smem, lo_v, db, (kb * 32 + 16 * half) * D * 2);
         st.o[db] = mfma32(va, st.p[kb][half], st.o[db]);
       }
-  sched_reads_ahead<KB * 2 * DB, 2, 4>();
+  sched_reads_ahead<KB * 2 * DB, 2, 2>();
   __builtin_amdgcn_sched_barrier(0);
 }
 
@@ -222,20 +222,19 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
     auto key0_of = [&](int t) { return lo + (int64_t)t * BN; };
     constexpr int PASSES = BN * (D / 8) / T;             // copy instructions per tile and wave
     TileDma<D, BN, T> dma;
-    dma.init(a.kv_stride_s, tid);
+    dma.init(tid);
+    const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2;
     // quarter `part` of the copies of K(t), V(t) into set t & 1 (parts 0,1: K; 2,3: V)
     auto issue_part = [&](int t, int part) {
       if (t >= nt) return;
       const bf16_t* base = part < 2 ? kbase : vbase;
       char* dst = smem + (part < 2 ? K_BASE : V_BASE) + (t & 1) * TILE_BYTES;
       const int64_t key0 = key0_of(t);
-      const bool whole = key0 + BN <= a.kv_capacity;     // every row of the tile exists in memory
+      const int64_t avail = a.kv_capacity - key0;
 #pragma unroll
       for (int n = 0; n < PASSES; ++n)
-        if (PASSES == 1 ? (part & 1) == 0 : (n & 1) == (part & 1)) {
-          if (whole) dma.issue(dst, base + key0 * a.kv_stride_s, tid, n);
-          else tile_load_async_pass<D, T>(dst, base, a.kv_stride_s, key0, hi - 1, tid, n);
-        }
+        if (PASSES == 1 ? (part & 1) == 0 : (n & 1) == (part & 1))
+          dma.issue(dst, base + key0 * a.kv_stride_s, row_bytes, avail > BN ? BN : (int)avail, tid, n);
     };
 
     for (int part = 0; part < 4; ++part) issue_part(0, part);
@@ -350,41 +349,49 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_pp_kernel(const FwdArgs a) {
     RpOffsets<D> lo_k;
     TrOffsets<D> lo_v;
     auto key0_of = [&](int t) { return lo + (int64_t)t * BN; };
-    constexpr int PASSES = BN * (D / 8) / T;
-    TileDma<D, BN, T> dma;
-    dma.init(a.kv_stride_s, tid);
-    // one tile (is_k: K(t) else V(t)) into buffer set `set`, passes with n % 2 == half
-    auto copy_half = [&](bool is_k, int t, int set, int half) {
-      if (t >= nt) return;
-      const bf16_t* base = is_k ? kbase : vbase;
-      char* dst = smem + (is_k ? K_BASE : V_BASE) + set * TILE_BYTES;
-      const int64_t key0 = key0_of(t);
-      const bool whole = key0 + BN <= a.kv_capacity;
-#pragma unroll
-      for (int n = 0; n < PASSES; ++n)
-        if (PASSES == 1 ? half == 0 : (n & 1) == half) {
-          if (whole) dma.issue(dst, base + key0 * a.kv_stride_s, tid, n);
-          else tile_load_async_pass<D, T>(dst, base, a.kv_stride_s, key0, hi - 1, tid, n);
-        }
+    // Tile copies are issued from vector phases only, by the four waves of the group that is in one
+    // (next to the LDS reads and MFMAs of a matrix phase they stall the wave): group B copies V(t+1)
+    // during its V(t), group A copies K(t+1) during its V(t).  Copies are branch-free: a tile past the
+    // end of the range re-copies the last tile (nobody reads it), rows past the allocation are clamped.
+    constexpr int GT = T / 2;                            // threads of one group
+    const int gtid = tid & (GT - 1);
+    TileDma<D, BN, GT> dma;
+    constexpr int PASSES = TileDma<D, BN, GT>::PASSES;   // copy instructions per tile and wave
+    static_assert(PASSES <= 4, "one copy instruction per softmax hook");
+    dma.init(gtid);
+    const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2;
+    struct CopyJob { const bf16_t* src; char* dst; int rows; };
+    auto make_copy = [&](bool is_k, int t, int set) {
+      const int64_t key0 = key0_of(t < nt ? t : nt - 1);
+      const int64_t avail = a.kv_capacity - key0;
+      CopyJob j;
+      j.src = (is_k ? kbase : vbase) + key0 * a.kv_stride_s;
+      j.dst = smem + (is_k ? K_BASE : V_BASE) + set * TILE_BYTES;
+      j.rows = avail > BN ? BN : (int)avail;
+      return j;
     };
-    // pair t = (V(t), K(t+1)) lives in set t & 1; quarter `part` of its copies
-    auto issue_pair_part = [&](int t, int part) {
-      if (part < 2) copy_half(false, t, t & 1, part);
-      else copy_half(true, t + 1, t & 1, part - 2);
+    auto copy_pass = [&](const CopyJob& j, int n) {
+#ifndef SLIMPIPE_NODMA
+      dma.issue(j.dst, j.src, row_bytes, j.rows, gtid, n);
+#endif
     };
-    auto softmax_tile = [&](int t, auto&& hook) {
+    // vector phase of tile t that also copies one tile of the next pair
+    auto vector_phase = [&](int t, const CopyJob& j) {
       const int64_t key0 = key0_of(t);
       const bool need_mask = (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
       int64_t kmax = a.kv_end - 1;
       if (a.causal && qpos < kmax) kmax = qpos;
       kmax -= key0;
       const int kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
-      fwd_softmax<D, BN, true>(st, c, need_mask, kmax_rel, g, hook);
+      fwd_softmax<D, BN, true>(st, c, need_mask, kmax_rel, g, [&](int part) { if (part < PASSES) copy_pass(j, part); });
     };
 
-    // prologue: K(0) into K set 1 (the set "pair -1" would use)
-    copy_half(true, 0, 1, 0);
-    copy_half(true, 0, 1, 1);
+    // prologue: K(0) into K set 1 (the set "pair -1" would use), half of it by each group
+    {
+      // both groups copy the whole tile (the same bytes twice): simplest way to keep the copy code single
+      const CopyJob j = make_copy(true, 0, 1);
+      for (int n = 0; n < PASSES; ++n) copy_pass(j, n);
+    }
     wait_async();
     lo_k.init(lane, K_BASE + TILE_BYTES);   // S(t) reads K(t) from set (t-1)&1: starts at set 1
     lo_v.init(lane, V_BASE);                // PV(t) reads V(t) from set t&1: starts at set 0
@@ -392,31 +399,48 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_pp_kernel(const FwdArgs a) {
 
     if (!group_b) {
       // phase 0
-      for (int part = 0; part < 4; ++part) issue_pair_part(0, part);
       fwd_scores<D, BN>(smem, lo_k, st);
       lo_k.add(-TILE_BYTES);
       phase_end();
+#ifdef SLIMPIPE_TRACE
+      long long tp_v = 0, tp_w = 0, tp_b1 = 0, tp_pv = 0, tp_s = 0, tp_b2 = 0, tp_t0 = clock64(), tp_w0 = wall_clock64(), tp_last = clock64();
+#define TP_MARK(var) { long long _n = clock64(); var += _n - tp_last; tp_last = _n; }
+#else
+#define TP_MARK(var)
+#endif
       for (int t = 0; t < nt; ++t) {
-        // phase 2t+1: vector phase; pair t must have landed when it ends
-        softmax_tile(t, [](int) {});
+        // phase 2t+1: vector phase, copying K(t+1) for the matrix phase that follows
+        vector_phase(t, make_copy(true, t + 1, t & 1));
+        TP_MARK(tp_v)
         wait_async();
+        TP_MARK(tp_w)
         phase_end();
-        // phase 2t+2: matrix phase; the copies of pair t+1 ride along
-        issue_pair_part(t + 1, 0);
-        issue_pair_part(t + 1, 1);
+        TP_MARK(tp_b1)
+        // phase 2t+2: matrix phase
         fwd_pv<D, BN>(smem, lo_v, st);
-        issue_pair_part(t + 1, 2);
-        issue_pair_part(t + 1, 3);
+        TP_MARK(tp_pv)
         if (t + 1 < nt) fwd_scores<D, BN>(smem, lo_k, st);
         const int d = (t & 1) ? -TILE_BYTES : TILE_BYTES;
         lo_k.add(d);
         lo_v.add(d);
+        TP_MARK(tp_s)
         phase_end();
+        TP_MARK(tp_b2)
       }
+#ifdef SLIMPIPE_TRACE
+      if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {
+        long long* dbg = reinterpret_cast<long long*>(a.lse + (int64_t)a.n_q_heads * a.s_q);   // caller over-allocates lse
+        dbg[0] = tp_v; dbg[1] = tp_w; dbg[2] = tp_b1; dbg[3] = tp_pv; dbg[4] = tp_s; dbg[5] = tp_b2;
+        dbg[6] = clock64() - tp_t0; dbg[7] = wall_clock64() - tp_w0; dbg[8] = nt;
+      }
+#endif
       phase_end();                          // group B's last matrix phase
     } else {
-      // phase 0: nothing to compute yet
-      for (int part = 0; part < 4; ++part) issue_pair_part(0, part);
+      // phase 0: nothing to compute yet; V(0)
+      {
+        const CopyJob j = make_copy(false, 0, 0);
+        for (int n = 0; n < PASSES; ++n) copy_pass(j, n);
+      }
       phase_end();
       // phase 1
       fwd_scores<D, BN>(smem, lo_k, st);
@@ -424,8 +448,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_pp_kernel(const FwdArgs a) {
       wait_async();
       phase_end();
       for (int t = 0; t < nt; ++t) {
-        // phase 2t+2: vector phase, issuing its share of the copies of pair t+1
-        softmax_tile(t, [&](int part) { issue_pair_part(t + 1, part); });
+        // phase 2t+2: vector phase, copying V(t+1)
+        vector_phase(t, make_copy(false, t + 1, (t + 1) & 1));
         phase_end();
         // phase 2t+3: matrix phase
         fwd_pv<D, BN>(smem, lo_v, st);

@@ -240,33 +240,36 @@ SP_DEV void tile_load_async_pass(char* tile, const bf16_t* base, int64_t row_str
       (unsigned)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char*)dst));
   dma16(src, lds);
 }
-// Loop-invariant part of that staging: the byte offset of this lane's chunk of pass n relative to
-// the first row of a tile, and the wave's LDS slot.  A tile copy is then "uniform base + lane offset"
-// (scalar base register + 32-bit vector offset), with no per-tile address arithmetic on the VALU.
-// Only valid when all ROWS rows of the tile exist in memory (callers take the clamped path otherwise).
+// The same staging with nothing but two per-lane constants: THREADS/NC rows per pass with
+// THREADS a multiple of 16*NC... (THREADS = 256, NC = 16: 16 rows per pass), so pass n handles row
+// r0 + (THREADS/NC)*n of the tile and, the row step being a multiple of 16, the SAME swizzled chunk.
+// A tile copy is "uniform base + 32-bit lane offset" with the row clamped to the rows that exist
+// (`rows_avail` >= 1, uniform): branch-free, four VALU operations per copy instruction.
 template <int D, int ROWS, int THREADS>
 struct TileDma {
-  static constexpr int NC = D / 8, PASSES = ROWS * NC / THREADS;
-  uint32_t goff[PASSES];
-  SP_DEV void init(int64_t row_stride, int tid) {
-#pragma unroll
-    for (int n = 0; n < PASSES; ++n) {
-      const int id = tid + n * THREADS;
-      const int r = id / NC, p = id % NC;
-      int c;
-      if constexpr (D == 128) c = ((((p >> 2) ^ r) & 3) << 2) | (((p & 3) ^ (r >> 2)) & 3);
-      else c = (p ^ r) & (NC - 1);
-      goff[n] = (uint32_t)((r * row_stride + c * 8) * 2);
-    }
+  static constexpr int NC = D / 8, RPP = THREADS / NC, PASSES = ROWS / RPP;
+  static_assert(RPP % 16 == 0 && ROWS % RPP == 0, "row step keeps the swizzle phase");
+  int r0;            // row of this lane in pass 0
+  uint32_t c16;      // byte offset of this lane's (swizzled) chunk inside the row
+  SP_DEV void init(int tid) {
+    const int r = tid / NC, p = tid % NC;
+    int c;
+    if constexpr (D == 128) c = ((((p >> 2) ^ r) & 3) << 2) | (((p & 3) ^ (r >> 2)) & 3);
+    else c = (p ^ r) & (NC - 1);
+    r0 = r;
+    c16 = (uint32_t)c * 16;
   }
   // pass n of the tile whose first row starts at `tile_base` (uniform) into LDS `tile`
-  SP_DEV void issue(char* tile, const bf16_t* tile_base, int tid, int n) const {
+  SP_DEV void issue(char* tile, const bf16_t* tile_base, uint32_t row_bytes, int rows_avail, int tid, int n) const {
     const int wave = tid >> 6;
     char* dst = tile + (n * THREADS + wave * 64) * 16;            // wave-uniform
     const unsigned lds = __builtin_amdgcn_readfirstlane(
         (unsigned)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char*)dst));
+    int r = r0 + RPP * n;
+    r = r < rows_avail ? r : rows_avail - 1;
+    const uint32_t off = (uint32_t)r * row_bytes + c16;
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :: "v"(goff[n]), "s"(tile_base), "s"(lds) : "memory", "m0");
+                 :: "v"(off), "s"(tile_base), "s"(lds) : "memory", "m0");
   }
 };
 
