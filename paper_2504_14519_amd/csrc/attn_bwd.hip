@@ -65,35 +65,165 @@ hipError_t launch_delta(const BwdArgs& a, int batch, int head_dim, hipStream_t s
 }
 
 // ------------------------------------------------------------------------------------ dq
+// Query-stationary: 8 waves x 32 query rows of one head; Q lives in registers and dO in LDS as B
+// operands (both in registers do not fit 256 registers a wave next to the accumulators), dQ^T
+// accumulates in registers, K/V tiles of BN keys stream through LDS.  Per tile u a wave runs
+//   matrix phase MM(u): dQ^T += K(u-1)^T dS(u-1)^T   (transposed read of K(u-1))
+//                       S(u)^T = K(u) Q^T,  dP(u)^T = V(u) dO^T          (row-packed reads)
+//   vector phase VV(u): dS(u)^T = exp2(c S - lse2) (dP - delta), packed to bf16
+// Waves 0-3 (group A) and 4-7 (group B) run the same sequence one phase apart with one workgroup
+// barrier per phase, so each SIMD hosts one wave in each kind of phase (the VALU work of one covers
+// the matrix pipe time of the other).  K lives in a ring of four LDS slots, V in a ring of two; the
+// group that is in a vector phase issues the asynchronous copies of the tiles two steps ahead
+// (A: K(u+2), B: V(u+2)) and waits for them at the end of its next matrix phase.
+template <int D, int BN>
+struct DqState {
+  static constexpr int KS = D / 16, DB = D / 32, KB = BN / 32;
+  bf16x8 qreg[KS];
+  f32x16 dq[DB];
+  f32x16 s[KB], dp[KB];
+  bf16x8 ds[KB][2];
+  float lse2, delta;
+};
+
+// One matrix phase as an explicit software pipeline.  The MFMAs are numbered m = 0 .. N-1 (first the
+// 2*KB*DB of dQ^T += K(u-1)^T dS^T, then per head_dim block ks the 2*KB of S0, dP0, S1, dP1, ...);
+// the LDS reads of MFMA m+LOOK are issued right before MFMA m into a ring of LOOK+1 operand buffers,
+// and scheduling fences keep that order.  (Leaving the order to the scheduler gave reads right in
+// front of their MFMA whenever registers were short: about 60 cycles an MFMA instead of 32.)
+template <int D, int BN, bool WITH_DQ, bool WITH_SCORES, int LOOK>
+struct DqMatrixPhase {
+  static constexpr int KB = BN / 32, DB = D / 32, KS = D / 16;
+  static constexpr int N_DQ = WITH_DQ ? 2 * KB * DB : 0, N_SC = WITH_SCORES ? 2 * KB * KS : 0, N = N_DQ + N_SC;
+  static constexpr int NBUF = LOOK + 1;
+  const char* smem;
+  const TrBase<D>& lo_kt;
+  const RpBase<D>& lo_k;
+  const RpBase<D>& lo_v;
+  const RpBase<D>& lo_do;
+  DqState<D, BN>& st;
+  bf16x8 abuf[NBUF];
+  bf16x8 dob[2];
+
+  template <int M>
+  SP_DEV void reads() {
+    if constexpr (M < N_DQ) {
+      constexpr int db = M % DB, blk = M / DB;                 // blk = 2*kb + half: 16 keys each
+      abuf[M % NBUF] = lds_tr<D>(smem, lo_kt, db, blk * 16 * D * 2);
+    } else if constexpr (M < N) {
+      constexpr int j = M - N_DQ, ks = j / (2 * KB), r = j % (2 * KB), kb = r / 2;
+      if constexpr ((r & 1) == 0) {
+        abuf[M % NBUF] = lds_rp<D>(smem, lo_k, ks, kb * 32 * D * 2);
+      } else {
+        abuf[M % NBUF] = lds_rp<D>(smem, lo_v, ks, kb * 32 * D * 2);
+        if constexpr (kb == 0) dob[ks & 1] = lds_rp<D>(smem, lo_do, ks, 0);
+      }
+    }
+  }
+  template <int M>
+  SP_DEV void mfma() {
+    if constexpr (M < N_DQ) {
+      constexpr int db = M % DB, blk = M / DB;
+      st.dq[db] = mfma32(abuf[M % NBUF], st.ds[blk / 2][blk % 2], st.dq[db]);
+    } else {
+      constexpr int j = M - N_DQ, ks = j / (2 * KB), r = j % (2 * KB), kb = r / 2;
+      const f32x16 zero = {0};
+      if constexpr ((r & 1) == 0) st.s[kb] = mfma32(abuf[M % NBUF], st.qreg[ks], ks == 0 ? zero : st.s[kb]);
+      else st.dp[kb] = mfma32(abuf[M % NBUF], dob[ks & 1], ks == 0 ? zero : st.dp[kb]);
+    }
+  }
+  template <int M>
+  SP_DEV void step() {
+    if constexpr (M < N) {
+      reads<M + LOOK>();
+      SP_FENCE();
+      mfma<M>();
+      SP_FENCE();
+      step<M + 1>();
+    }
+  }
+  template <int M>
+  SP_DEV void prologue() {
+    if constexpr (M < LOOK) { reads<M>(); prologue<M + 1>(); }
+  }
+  SP_DEV void run() {
+    SP_FENCE();
+    prologue<0>();
+    SP_FENCE();
+    step<0>();
+  }
+};
+
+template <int D, int BN, bool WITH_DQ, bool WITH_SCORES>
+SP_DEV void dq_matrix_phase(const char* smem, const TrBase<D>& lo_kt, const RpBase<D>& lo_k, const RpBase<D>& lo_v,
+                            const RpBase<D>& lo_do, DqState<D, BN>& st) {
+  DqMatrixPhase<D, BN, WITH_DQ, WITH_SCORES, 2> ph{smem, lo_kt, lo_k, lo_v, lo_do, st};
+  ph.run();
+}
+
+// dS^T = p (dP^T - delta) with p = exp2(c S^T - lse2) on visible pairs; `hook(i)`, i = 0..3, is called at
+// four points spread over the phase (asynchronous tile copies ride there).
+template <int D, int BN, class H>
+SP_DEV void dq_vector_phase(DqState<D, BN>& st, float c, bool need_mask, int kmax_rel, int g, H&& hook) {
+  constexpr int KB = BN / 32;
+  if (need_mask) {
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key_rel = kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
+        st.s[kb][i] = key_rel <= kmax_rel ? st.s[kb][i] : -INFINITY;     // exp2(-inf) = 0
+      }
+  }
+#pragma unroll
+  for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      hook(kb * 2 + half);
+#pragma unroll
+      for (int i = 8 * half; i < 8 * half + 8; ++i) {
+        const float p = exp2_fast(__builtin_fmaf(st.s[kb][i], c, -st.lse2));
+        st.s[kb][i] = p * (st.dp[kb][i] - st.delta);
+      }
+      st.ds[kb][half] = pack8(st.s[kb], 8 * half);
+      // pin: without a use here the optimiser sinks this arithmetic past the phase barrier
+      asm volatile("" : "+v"(st.ds[kb][half]));
+    }
+}
+
 template <int D, int NW, int BN>
 __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
-  constexpr int BM = NW * 32, KS = D / 16, DB = D / 32, KB = BN / 32, T = NW * 64;
+  static_assert(NW == 8, "two groups of four waves");
+  constexpr int BM = NW * 32, KS = D / 16, DB = D / 32, T = NW * 64, GT = T / 2;
   constexpr int TILE_BYTES = BN * D * 2;
+  constexpr int KSLOTS = 4, VSLOTS = 2;
+  constexpr int K_BASE = 0, V_BASE = KSLOTS * TILE_BYTES, DO_BASE = (KSLOTS + VSLOTS) * TILE_BYTES;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  char* k_tiles = smem;
-  char* v_tiles = smem + 2 * TILE_BYTES;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ql = lane & 31;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);      // known uniform to the compiler
+  const bool group_b = wave_u >= NW / 2;
+  const int gtid = tid & (GT - 1);
   const int qblk = (int)gridDim.x - 1 - (int)blockIdx.x;
   const int h = blockIdx.y, b = blockIdx.z, hk = h / a.group;
-  const int m0 = qblk * BM, wrow0 = m0 + wave * 32;
+  const int m0 = qblk * BM, wrow0 = m0 + wave_u * 32;
   const int myrow = wrow0 + ql;
   const int myrow_c = myrow < a.s_q ? myrow : a.s_q - 1;
   const int64_t qpos = a.q_offset + myrow;
 
-  bf16x8 qreg[KS], doreg[KS];
+  DqState<D, BN> st;
   {
     const bf16_t* qp = a.q + (int64_t)b * a.q_stride_b + (int64_t)myrow_c * a.q_stride_s + (int64_t)h * a.q_stride_h;
-    const bf16_t* dp = a.d_out + (int64_t)b * a.do_stride_b + (int64_t)myrow_c * a.do_stride_s + (int64_t)h * a.do_stride_h;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks + 8 * g);
-      doreg[ks] = *reinterpret_cast<const bf16x8*>(dp + 16 * ks + 8 * g);
-    }
+    for (int ks = 0; ks < KS; ++ks) st.qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks + 8 * g);
+    const int64_t stat = ((int64_t)b * a.n_q_heads + h) * a.s_q + myrow_c;
+    st.lse2 = a.lse2[stat];          // +inf for an empty row -> p = 0
+    st.delta = a.delta[stat];
   }
-  const int64_t stat = ((int64_t)b * a.n_q_heads + h) * a.s_q + myrow_c;
-  const float lse2 = a.lse2[stat];          // +inf for an empty row -> p = 0
-  const float delta = a.delta[stat];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) st.dq[db][i] = 0.f;
 
   const int64_t lo = a.kv_begin;
   int64_t hi = a.kv_end;
@@ -103,90 +233,113 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
     hi = hi < lim ? hi : lim;
   }
   const int nt = hi > lo ? (int)((hi - lo + BN - 1) / BN) : 0;
-  const bf16_t* kbase = a.k + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
-  const bf16_t* vbase = a.v + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
-
-  f32x16 dq[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) dq[db][i] = 0.f;
   const float c = a.scale_log2e;
 
-  TileStage<D, BN, T> ks_stage, vs_stage;
   if (nt > 0) {
-    ks_stage.issue(kbase, a.kv_stride_s, lo, hi - 1, tid);
-    vs_stage.issue(vbase, a.kv_stride_s, lo, hi - 1, tid);
-    ks_stage.commit(k_tiles, tid);
-    vs_stage.commit(v_tiles, tid);
-  }
-  __syncthreads();
-
-  for (int t = 0; t < nt; ++t) {
-    const int64_t key0 = lo + (int64_t)t * BN;
-    const char* kt = k_tiles + (t & 1) * TILE_BYTES;
-    const char* vt = v_tiles + (t & 1) * TILE_BYTES;
-    const bool more = (t + 1 < nt);
-    if (more) {
-      ks_stage.issue(kbase, a.kv_stride_s, key0 + BN, hi - 1, tid);
-      vs_stage.issue(vbase, a.kv_stride_s, key0 + BN, hi - 1, tid);
-    }
-    const bool skip = a.causal && key0 > a.q_offset + wrow0 + 31;
-    if (!skip) {
-      f32x16 s[KB], dp[KB];
-#pragma unroll
-      for (int kb = 0; kb < KB; ++kb) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { s[kb][i] = 0.f; dp[kb][i] = 0.f; }
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          bf16x8 ka = lds_read_rowpacked<D>(kt, kb * 32 + ql, ks, g);
-          s[kb] = mfma32(ka, qreg[ks], s[kb]);
-        }
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          bf16x8 va = lds_read_rowpacked<D>(vt, kb * 32 + ql, ks, g);
-          dp[kb] = mfma32(va, doreg[ks], dp[kb]);
-        }
-      }
+    const bf16_t* kbase = a.k + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
+    const bf16_t* vbase = a.v + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
+    auto key0_of = [&](int t) { return lo + (int64_t)t * BN; };
+    TileDma<D, BN, GT> dma;
+    constexpr int PASSES = TileDma<D, BN, GT>::PASSES;
+    static_assert(PASSES <= 4, "one copy instruction per hook of the vector phase");
+    dma.init(gtid);
+    const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2;
+    struct CopyJob { const bf16_t* src; char* dst; int rows; };
+    // tile t of K (slot t % KSLOTS) or V (slot t % VSLOTS); past the end the last tile is copied again
+    auto make_copy = [&](bool is_k, int t) {
+      const int64_t key0 = key0_of(t < nt ? t : nt - 1);
+      const int64_t avail = a.kv_capacity - key0;
+      CopyJob j;
+      j.src = (is_k ? kbase : vbase) + key0 * a.kv_stride_s;
+      j.dst = smem + (is_k ? K_BASE + (t % KSLOTS) * TILE_BYTES : V_BASE + (t % VSLOTS) * TILE_BYTES);
+      j.rows = avail > BN ? BN : (int)avail;
+      return j;
+    };
+    auto copy_pass = [&](const CopyJob& j, int n) { dma.issue(j.dst, j.src, row_bytes, j.rows, gtid, n); };
+    auto copy_all = [&](const CopyJob& j) {
+      for (int n = 0; n < PASSES; ++n) copy_pass(j, n);
+    };
+    auto vector_phase = [&](int u, const CopyJob& j) {
+      const int64_t key0 = key0_of(u);
       const bool need_mask = (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
-      if (need_mask) {
-        int64_t kmax = a.kv_end - 1;
-        if (a.causal && qpos < kmax) kmax = qpos;
-        kmax -= key0;
-        const int kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int key_rel = kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-            s[kb][i] = key_rel <= kmax_rel ? s[kb][i] : -INFINITY;     // exp2(-inf) = 0
-          }
-      }
-#pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float p = exp2_fast(__builtin_fmaf(s[kb][i], c, -lse2));
-          s[kb][i] = p * (dp[kb][i] - delta);        // dS^T
-        }
-#pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          const bf16x8 dsb = pack8(s[kb], 8 * half);
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            bf16x8 kta = lds_read_transposed<D>(kt, kb * 32 + 16 * half, db, lane);
-            dq[db] = mfma32(kta, dsb, dq[db]);
-          }
-        }
+      int64_t kmax = a.kv_end - 1;
+      if (a.causal && qpos < kmax) kmax = qpos;
+      kmax -= key0;
+      const int kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
+      dq_vector_phase<D, BN>(st, c, need_mask, kmax_rel, g, [&](int part) { if (part < PASSES) copy_pass(j, part); });
+    };
+
+    // prologue: the dO rows of the block (all threads), K(0), K(1) (group A), V(0), V(1) (group B)
+    {
+      TileDma<D, BM, T> dma_do;
+      dma_do.init(tid);
+      const bf16_t* dobase = a.d_out + (int64_t)b * a.do_stride_b + (int64_t)m0 * a.do_stride_s + (int64_t)h * a.do_stride_h;
+      for (int n = 0; n < TileDma<D, BM, T>::PASSES; ++n)
+        dma_do.issue(smem + DO_BASE, dobase, (uint32_t)a.do_stride_s * 2, a.s_q - m0, tid, n);
     }
-    if (more) {
-      ks_stage.commit(k_tiles + ((t + 1) & 1) * TILE_BYTES, tid);
-      vs_stage.commit(v_tiles + ((t + 1) & 1) * TILE_BYTES, tid);
-    }
+    if (!group_b) { copy_all(make_copy(true, 0)); copy_all(make_copy(true, 1)); }
+    else { copy_all(make_copy(false, 0)); copy_all(make_copy(false, 1)); }
+    wait_async();
+    TrBase<D> lo_kt;         // K(u-1), transposed
+    RpBase<D> lo_k, lo_v;    // K(u), V(u), row-packed
+    lo_kt.init(lane, K_BASE + (KSLOTS - 1) * TILE_BYTES);      // "K(-1)": never read
+    lo_k.init(lane, K_BASE);
+    lo_v.init(lane, V_BASE);
+    RpBase<D> lo_do;         // this wave's 32 rows of dO
+    lo_do.init(lane, DO_BASE + wave * 32 * D * 2);
     __syncthreads();
+
+    // ring bookkeeping after matrix phase u: every pointer moves one tile on
+    int kslot = 0;           // slot of K(u)
+    auto advance = [&]() {
+      const int dk = (kslot == KSLOTS - 1) ? -(KSLOTS - 1) * TILE_BYTES : TILE_BYTES;
+      const int dkt = (kslot == 0) ? -(KSLOTS - 1) * TILE_BYTES : TILE_BYTES;   // K(u-1) slot = kslot - 1
+      lo_k.add(dk);
+      lo_kt.add(dkt);
+      lo_v.add((kslot & 1) ? -TILE_BYTES : TILE_BYTES);
+      kslot = (kslot == KSLOTS - 1) ? 0 : kslot + 1;
+    };
+    // Both groups run the same code; group B starts one phase (one barrier) later and group A idles
+    // one phase at the end.  Group A copies K tiles, group B V tiles.
+    const bool copies_k = !group_b;
+#ifdef SLIMPIPE_TRACE
+    long long tq_v = 0, tq_b1 = 0, tq_m = 0, tq_w = 0, tq_b2 = 0, tq_t0 = clock64(), tq_w0 = wall_clock64(), tq_last = clock64();
+#define TQ_MARK(var) { long long _n = clock64(); var += _n - tq_last; tq_last = _n; }
+#else
+#define TQ_MARK(var)
+#endif
+    if (group_b) phase_end();
+    dq_matrix_phase<D, BN, false, true>(smem, lo_kt, lo_k, lo_v, lo_do, st);       // scores of tile 0
+    advance();
+    wait_async();
+    phase_end();
+    TQ_MARK(tq_b2)
+    for (int u = 0; u + 1 < nt; ++u) {
+      vector_phase(u, make_copy(copies_k, u + 2));       // tile u+2 rides along
+      TQ_MARK(tq_v)
+      phase_end();
+      TQ_MARK(tq_b1)
+      dq_matrix_phase<D, BN, true, true>(smem, lo_kt, lo_k, lo_v, lo_do, st);      // dQ of tile u, scores of tile u+1
+      advance();
+      TQ_MARK(tq_m)
+      wait_async();                                      // the copies of the vector phase before have landed
+      TQ_MARK(tq_w)
+      phase_end();
+      TQ_MARK(tq_b2)
+    }
+    vector_phase(nt - 1, make_copy(copies_k, nt + 1));   // (clamped: copies the last tile once more)
+    phase_end();
+    dq_matrix_phase<D, BN, true, false>(smem, lo_kt, lo_k, lo_v, lo_do, st);       // dQ of the last tile
+    wait_async();
+    phase_end();
+    if (!group_b) phase_end();
+#ifdef SLIMPIPE_TRACE
+    if (blockIdx.x == gridDim.x - 1 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {
+      long long* dbg = reinterpret_cast<long long*>(a.lse2 + (int64_t)a.n_q_heads * a.s_q) + 8;   // behind the workspace proper
+      dbg[0] = tq_v; dbg[1] = tq_b1; dbg[2] = tq_m; dbg[3] = tq_w; dbg[4] = tq_b2;
+      dbg[5] = clock64() - tq_t0; dbg[6] = wall_clock64() - tq_w0; dbg[7] = nt;
+    }
+#endif
   }
 
   if (myrow < a.s_q) {
@@ -196,8 +349,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
         const int d = 32 * db + 8 * i4 + 4 * g;
-        f32x4 v4 = {dq[db][4 * i4] * a.scale, dq[db][4 * i4 + 1] * a.scale, dq[db][4 * i4 + 2] * a.scale,
-                    dq[db][4 * i4 + 3] * a.scale};
+        f32x4 v4 = {st.dq[db][4 * i4] * a.scale, st.dq[db][4 * i4 + 1] * a.scale, st.dq[db][4 * i4 + 2] * a.scale,
+                    st.dq[db][4 * i4 + 3] * a.scale};
         if (a.dq_f32) {
           f32x4* dst = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.dq) + base + d);
           if (a.dq_accumulate) v4 += *dst;
@@ -212,7 +365,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
 template <int D, int NW, int BN>
 static hipError_t launch_dq_t(const BwdArgs& a, int batch, hipStream_t st) {
   constexpr int BM = NW * 32;
-  const size_t smem = (size_t)4 * BN * D * 2;
+  const size_t smem = (size_t)6 * BN * D * 2 + (size_t)BM * D * 2;   // 4 K slots + 2 V slots + dO rows
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dq_kernel<D, NW, BN>),
@@ -241,12 +394,6 @@ hipError_t launch_bwd_dq(const BwdArgs& a, int batch, int head_dim, hipStream_t 
 // Query tiles (BMQ rows of Q and dO) sit in a ring of three LDS buffers: while tile t is consumed,
 // tile t+1 is already resident (its first block's scores are computed ahead) and tile t+2 is in
 // flight, so one barrier per tile is enough.
-
-#define SP_FENCE() __builtin_amdgcn_sched_barrier(0)
-// scheduling-group classes of __builtin_amdgcn_sched_group_barrier
-#define SP_SG_VALU 0x2
-#define SP_SG_MFMA 0x8
-#define SP_SG_DSRD 0x100
 
 // Operands of one 32-row query block for S = Q K^T and dP = dO V^T (row-packed reads).
 template <int D>

@@ -29,25 +29,8 @@ struct FwdState {
   f32x16 s[KB];
   bf16x8 p[KB][2];
   float m_run, l_run;
+  float mx;          // row maximum of the raw scores of the tile in `s` (two-group variant)
 };
-
-// scheduling-group classes of __builtin_amdgcn_sched_group_barrier
-#define SP_SG_MFMA 0x8
-#define SP_SG_DSRD 0x100
-
-// Ask the scheduler for "LDS reads LOOK MFMAs ahead of their use": a block of reads first, then one
-// MFMA followed by the reads of the MFMA LOOK places later.  An LDS read takes several MFMA times to
-// come back and a wave issues in order, so reads placed right before their MFMA stall it.
-template <int N_MFMA, int READS_PER_MFMA, int LOOK>
-SP_DEV void sched_reads_ahead() {
-  __builtin_amdgcn_sched_group_barrier(SP_SG_DSRD, LOOK * READS_PER_MFMA, 0);
-#pragma unroll
-  for (int i = 0; i < N_MFMA - LOOK; ++i) {
-    __builtin_amdgcn_sched_group_barrier(SP_SG_MFMA, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(SP_SG_DSRD, READS_PER_MFMA, 0);
-  }
-  __builtin_amdgcn_sched_group_barrier(SP_SG_MFMA, LOOK, 0);
-}
 
 // S(t)^T = K(t) Q^T for this wave's 32 queries.
 template <int D, int BN>
@@ -87,11 +70,10 @@ SP_DEV void fwd_pv(const char* smem, const TrOffsets<D>& lo_v, FwdState<D, BN>& 
   __builtin_amdgcn_sched_barrier(0);
 }
 
-// P(t) = online softmax of S(t); rescales O and the running sum when a row maximum moves.
-// kmax_rel: last visible key of this lane's query relative to the tile (>= BN: no mask needed).
-template <int D, int BN, bool PIN, class H>
-SP_DEV void fwd_softmax(FwdState<D, BN>& st, float c, bool need_mask, int kmax_rel, int g, H&& hook) {
-  constexpr int KB = BN / 32, DB = D / 32;
+// Mask the scores of a tile and take this lane's row maximum (raw scores; both half-waves combined).
+template <int D, int BN>
+SP_DEV float fwd_rowmax(FwdState<D, BN>& st, bool need_mask, int kmax_rel, int g) {
+  constexpr int KB = BN / 32;
   if (need_mask) {
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
@@ -101,13 +83,21 @@ SP_DEV void fwd_softmax(FwdState<D, BN>& st, float c, bool need_mask, int kmax_r
         st.s[kb][i] = key_rel <= kmax_rel ? st.s[kb][i] : -INFINITY;
       }
   }
-  hook(0);
   float mx = -INFINITY;
 #pragma unroll
   for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) mx = fmaxf(mx, st.s[kb][i]);
-  mx = xhalf_max(mx);
+    for (int i = 0; i < 16; i += 2) mx = fmaxf(fmaxf(st.s[kb][i], st.s[kb][i + 1]), mx);   // v_max3_f32
+  return xhalf_max(mx);
+}
+
+// P(t) = online softmax of S(t); rescales O and the running sum when a row maximum moves.
+// kmax_rel: last visible key of this lane's query relative to the tile (>= BN: no mask needed).
+template <int D, int BN, bool PIN, bool PRE, class H>
+SP_DEV void fwd_softmax(FwdState<D, BN>& st, float c, bool need_mask, int kmax_rel, int g, H&& hook) {
+  constexpr int KB = BN / 32, DB = D / 32;
+  hook(0);
+  const float mx = PRE ? st.mx : fwd_rowmax<D, BN>(st, need_mask, kmax_rel, g);
   hook(1);
   const float m_new = fmaxf(st.m_run, mx * c);
   const float m_eff = (m_new == -INFINITY) ? 0.f : m_new;
@@ -261,7 +251,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
         if (a.causal && qpos < kmax) kmax = qpos;
         kmax -= key0;
         const int kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
-        fwd_softmax<D, BN, false>(st, c, need_mask, kmax_rel, g, [](int) {});
+        fwd_softmax<D, BN, false, false>(st, c, need_mask, kmax_rel, g, [](int) {});
         TR_MARK(tr_v)
         issue_part(t + 1, 2);
         issue_part(t + 1, 3);
@@ -297,12 +287,6 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
 // barrier per phase, so every SIMD hosts one wave in each kind of phase.  The pair (V(t), K(t+1))
 // that M(t) needs lives in one of two LDS buffer sets; the next pair is copied asynchronously during
 // the two phases before it is needed.
-SP_DEV void phase_end() {
-  __builtin_amdgcn_sched_barrier(0);
-  __syncthreads();
-  __builtin_amdgcn_sched_barrier(0);
-}
-
 template <int D, int NW, int BN>
 __global__ __launch_bounds__(NW * 64) void attn_fwd_pp_kernel(const FwdArgs a) {
   static_assert(NW == 8, "two groups of four waves");
@@ -377,13 +361,18 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_pp_kernel(const FwdArgs a) {
     };
     // vector phase of tile t that also copies one tile of the next pair
     auto vector_phase = [&](int t, const CopyJob& j) {
+      fwd_softmax<D, BN, true, true>(st, c, false, 0, g, [&](int part) { if (part < PASSES) copy_pass(j, part); });
+    };
+    // tail of a matrix phase: mask S(t) and take its row maxima (balances the two kinds of phase)
+    auto rowmax_tile = [&](int t) {
       const int64_t key0 = key0_of(t);
       const bool need_mask = (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
       int64_t kmax = a.kv_end - 1;
       if (a.causal && qpos < kmax) kmax = qpos;
       kmax -= key0;
       const int kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
-      fwd_softmax<D, BN, true>(st, c, need_mask, kmax_rel, g, [&](int part) { if (part < PASSES) copy_pass(j, part); });
+      st.mx = fwd_rowmax<D, BN>(st, need_mask, kmax_rel, g);
+      asm volatile("" : "+v"(st.mx));      // keep it on this side of the phase barrier
     };
 
     // prologue: K(0) into K set 1 (the set "pair -1" would use), half of it by each group
@@ -400,6 +389,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_pp_kernel(const FwdArgs a) {
     if (!group_b) {
       // phase 0
       fwd_scores<D, BN>(smem, lo_k, st);
+      rowmax_tile(0);
       lo_k.add(-TILE_BYTES);
       phase_end();
 #ifdef SLIMPIPE_TRACE
@@ -419,7 +409,10 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_pp_kernel(const FwdArgs a) {
         // phase 2t+2: matrix phase
         fwd_pv<D, BN>(smem, lo_v, st);
         TP_MARK(tp_pv)
-        if (t + 1 < nt) fwd_scores<D, BN>(smem, lo_k, st);
+        if (t + 1 < nt) {
+          fwd_scores<D, BN>(smem, lo_k, st);
+          rowmax_tile(t + 1);
+        }
         const int d = (t & 1) ? -TILE_BYTES : TILE_BYTES;
         lo_k.add(d);
         lo_v.add(d);
@@ -444,6 +437,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_pp_kernel(const FwdArgs a) {
       phase_end();
       // phase 1
       fwd_scores<D, BN>(smem, lo_k, st);
+      rowmax_tile(0);
       lo_k.add(-TILE_BYTES);
       wait_async();
       phase_end();
@@ -453,7 +447,10 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_pp_kernel(const FwdArgs a) {
         phase_end();
         // phase 2t+3: matrix phase
         fwd_pv<D, BN>(smem, lo_v, st);
-        if (t + 1 < nt) fwd_scores<D, BN>(smem, lo_k, st);
+        if (t + 1 < nt) {
+          fwd_scores<D, BN>(smem, lo_k, st);
+          rowmax_tile(t + 1);
+        }
         const int d = (t & 1) ? -TILE_BYTES : TILE_BYTES;
         lo_k.add(d);
         lo_v.add(d);

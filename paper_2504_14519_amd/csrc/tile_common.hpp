@@ -152,6 +152,42 @@ SP_DEV bf16x8 lds_tr(const char* smem, const TrOffsets<D>& lo, int db, int const
   return r;
 }
 
+// The same two read patterns from ONE register each.  With tile bases at multiples of 256 bytes the
+// swizzle makes the offset of head_dim block ks (row-packed) or db (transposed) the offset of block 0
+// XOR a compile-time constant, so a kernel short of registers keeps one offset per tile and pays one
+// v_xor per read instead of holding D/16 offsets.
+template <int D>
+struct RpBase {
+  int off0;
+  SP_DEV void init(int lane, int base) { off0 = base + tile_off<D>(lane & 31, lane >> 5); }
+  SP_DEV void add(int delta) { off0 += delta; }
+};
+template <int D>
+struct TrBase {
+  int off0;
+  SP_DEV void init(int lane, int base) {
+    const int j = lane & 15, b = lane >> 4;
+    off0 = base + tile_off<D>(((b >> 1) << 2) + (j >> 2), 2 * (b & 1) + ((j & 3) >> 1)) + ((j & 1) << 3);
+  }
+  SP_DEV void add(int delta) { off0 += delta; }
+};
+template <int D>
+SP_DEV bf16x8 lds_rp(const char* smem, const RpBase<D>& lo, int ks, int const_off) {
+  return *reinterpret_cast<const bf16x8*>(smem + (lo.off0 ^ (32 * ks)) + const_off);
+}
+template <int D>
+SP_DEV bf16x8 lds_tr(const char* smem, const TrBase<D>& lo, int db, int const_off) {
+  typedef bf16x4 __attribute__((address_space(3))) * lds_v4_ptr;
+  constexpr int X1 = D == 128 ? 32 : 0;       // rows +8 flip bit 1 of the swizzled chunk for D = 128
+  const int o = lo.off0 ^ (64 * db);
+  bf16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4_ptr)(smem + o + const_off));
+  bf16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4_ptr)(smem + (o ^ X1) + 8 * D * 2 + const_off));
+  bf16x8 r;
+  r[0] = a[0]; r[1] = a[1]; r[2] = a[2]; r[3] = a[3];
+  r[4] = b[0]; r[5] = b[1]; r[6] = b[2]; r[7] = b[3];
+  return r;
+}
+
 // Cooperative staging of a ROWS x D bf16 tile: global -> registers (issue early) -> LDS (commit late).
 // Row r of the tile is global row min(row0 + r, row_last); callers mask what the clamp duplicates.
 template <int D, int ROWS, int THREADS>
@@ -275,6 +311,35 @@ struct TileDma {
 
 // vmcnt(0), other counters untouched (gfx9 encoding: vmcnt[3:0]|[15:14], expcnt[6:4], lgkmcnt[11:8]).
 SP_DEV void wait_async() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// ---- scheduling helpers ------------------------------------------------------------------------
+#define SP_FENCE() __builtin_amdgcn_sched_barrier(0)
+// instruction classes of __builtin_amdgcn_sched_group_barrier
+#define SP_SG_VALU 0x2
+#define SP_SG_MFMA 0x8
+#define SP_SG_DSRD 0x100
+
+// Ask the scheduler for "LDS reads LOOK MFMAs ahead of their use": a block of reads first, then one
+// MFMA followed by the reads of the MFMA LOOK places later.  An LDS read takes several MFMA times to
+// come back and a wave issues in order, so reads placed right before their MFMA stall it.
+// (LOOK = 2 measured best; deeper look-ahead made the schedules worse.)
+template <int N_MFMA, int READS_PER_MFMA, int LOOK>
+SP_DEV void sched_reads_ahead() {
+  __builtin_amdgcn_sched_group_barrier(SP_SG_DSRD, LOOK * READS_PER_MFMA, 0);
+#pragma unroll
+  for (int i = 0; i < N_MFMA - LOOK; ++i) {
+    __builtin_amdgcn_sched_group_barrier(SP_SG_MFMA, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(SP_SG_DSRD, READS_PER_MFMA, 0);
+  }
+  __builtin_amdgcn_sched_group_barrier(SP_SG_MFMA, LOOK, 0);
+}
+
+// End of a phase of the two-group schedules: nothing may be scheduled across the barrier.
+SP_DEV void phase_end() {
+  __builtin_amdgcn_sched_barrier(0);
+  __syncthreads();
+  __builtin_amdgcn_sched_barrier(0);
+}
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
