@@ -384,228 +384,169 @@ hipError_t launch_bwd_dq(const BwdArgs& a, int batch, int head_dim, hipStream_t 
 }
 
 // ------------------------------------------------------------------------------------ dk / dv
-// The dk/dv kernel treats the query rows it has to visit (all query tiles that can see its keys,
-// for every head of the GQA group, in a fixed order) as ONE stream of 32-row blocks and runs a
-// software pipeline over that stream.  For block j:
-//   region X: score MFMAs of block j+1  ||  softmax of block j  ||  transposed operand reads of j
-//   region Y: accumulate MFMAs of block j  ||  score operand reads of block j+2
-// A wave issues in order, so the overlap has to be in the instruction stream itself; each region
-// is one scheduling region and the group barriers ask for "1 MFMA, then a few VALU / LDS reads".
-// Query tiles (BMQ rows of Q and dO) sit in a ring of three LDS buffers: while tile t is consumed,
-// tile t+1 is already resident (its first block's scores are computed ahead) and tile t+2 is in
-// flight, so one barrier per tile is enough.
-
-// Operands of one 32-row query block for S = Q K^T and dP = dO V^T (row-packed reads).
+// Key-stationary twin of the dq kernel: 8 waves x 32 keys of one KV head; K lives in registers and V
+// in LDS as B operands, dK^T and dV^T accumulate in registers, and the query rows that can see the
+// keys (every query tile, for every head of the GQA group, in a fixed order: the sums are
+// reproducible) stream through LDS as tiles of 32 rows of Q and dO.  Per tile u a wave runs
+//   matrix phase MM(u): dV^T += dO(u-1)^T P(u-1),  dK^T += Q(u-1)^T dS(u-1)    (transposed reads)
+//                       S(u) = Q(u) K^T,  dP(u) = dO(u) V^T                     (row-packed reads)
+//   vector phase VV(u): P = exp2(c S - lse2),  dS = P (dP - delta), packed to bf16
+// and the two wave groups run one phase apart exactly as in the dq kernel.  (One wave per SIMD with
+// twice the registers cannot overlap the two kinds of work: a wave that has issued an MFMA issues
+// nothing else until the matrix pipe has taken it, so vector work only hides behind the MFMAs of
+// ANOTHER wave of the same SIMD.)  Q and dO tiles sit in rings of four LDS slots, the row statistics
+// in a ring of four; group A copies Q(u+2) and the statistics, group B copies dO(u+2).
 template <int D>
-struct ScoreOps { bf16x8 qa[D / 16], da[D / 16]; };
+struct DkdvState {
+  static constexpr int KS = D / 16, DB = D / 32;
+  bf16x8 kreg[KS];
+  f32x16 dk[DB], dv[DB];
+  f32x16 s, dp;
+  bf16x8 pb[2], dsb[2];      // 16 query rows each
+};
 
-template <int D, int TILE_BYTES>
-SP_DEV void dkdv_load_ops(const char* smem, const RpOffsets<D>& lo, int blk_off, ScoreOps<D>& o) {
-#pragma unroll
-  for (int ks = 0; ks < D / 16; ++ks) {
-    o.qa[ks] = lds_rp<D>(smem, lo, ks, blk_off);
-    o.da[ks] = lds_rp<D>(smem, lo, ks, TILE_BYTES + blk_off);
-  }
-}
-template <int D>
-SP_DEV void dkdv_scores(const ScoreOps<D>& o, const bf16x8 (&kreg)[D / 16], const bf16x8 (&vreg)[D / 16],
-                        f32x16& s, f32x16& dp) {
-#pragma unroll
-  for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
-#pragma unroll
-  for (int ks = 0; ks < D / 16; ++ks) {
-    s = mfma32(o.qa[ks], kreg[ks], s);
-    dp = mfma32(o.da[ks], vreg[ks], dp);
-  }
-}
+// LDS layout (bytes): Q ring, dO ring, V rows of the workgroup, statistics ring
+template <int D, int NW>
+struct DkdvLds {
+  static constexpr int BMQ = 32, SLOTS = 4;
+  static constexpr int TILE_BYTES = BMQ * D * 2;
+  static constexpr int Q_BASE = 0, DO_BASE = SLOTS * TILE_BYTES, V_BASE = 2 * SLOTS * TILE_BYTES;
+  static constexpr int V_BYTES = NW * 32 * D * 2;
+  static constexpr int STAT_BASE = V_BASE + V_BYTES;          // [SLOTS][lse2[BMQ], delta[BMQ]] floats
+  static constexpr int STAT_BYTES = 2 * BMQ * 4;
+  static constexpr int TOTAL = STAT_BASE + SLOTS * STAT_BYTES;
+};
 
-// p = exp2(c s - lse2) on visible pairs (in s), dS = p (dP - delta) (in dp).
-template <bool MASK>
-SP_DEV void dkdv_softmax(f32x16& s, f32x16& dp, const float* lse_t, const float* del_t, int qb, int g, float c,
-                         int rmin_rel, int rmax_rel) {
-  if (MASK) {
+template <int D, int NW, bool WITH_ACC, bool WITH_SCORES, int LOOK>
+struct DkdvMatrixPhase {
+  using L = DkdvLds<D, NW>;
+  static constexpr int KS = D / 16, DB = D / 32;
+  static constexpr int N_AC = WITH_ACC ? 4 * DB : 0, N_SC = WITH_SCORES ? 2 * KS : 0, N = N_AC + N_SC;
+  static constexpr int NBUF = LOOK + 1, HALF = 16 * D * 2;
+  const char* smem;
+  const TrBase<D>& lo_qt;      // Q(u-1), transposed; dO(u-1) sits DO_BASE further
+  const RpBase<D>& lo_q;       // Q(u), row-packed; dO(u) sits DO_BASE further
+  const RpBase<D>& lo_v;       // this wave's 32 rows of V
+  DkdvState<D>& st;
+  bf16x8 abuf[NBUF];
+  bf16x8 vb[2];
+
+  template <int M>
+  SP_DEV void reads() {
+    if constexpr (M < N_AC) {
+      constexpr int h = M / (2 * DB), db = (M % (2 * DB)) / 2;
+      abuf[M % NBUF] = lds_tr<D>(smem, lo_qt, db, ((M & 1) ? 0 : L::DO_BASE) + h * HALF);
+    } else if constexpr (M < N) {
+      constexpr int j = M - N_AC, ks = j / 2;
+      if constexpr ((j & 1) == 0) {
+        abuf[M % NBUF] = lds_rp<D>(smem, lo_q, ks, 0);
+      } else {
+        abuf[M % NBUF] = lds_rp<D>(smem, lo_q, ks, L::DO_BASE);
+        vb[ks & 1] = lds_rp<D>(smem, lo_v, ks, 0);
+      }
+    }
+  }
+  template <int M>
+  SP_DEV void mfma() {
+    if constexpr (M < N_AC) {
+      constexpr int h = M / (2 * DB), db = (M % (2 * DB)) / 2;
+      if constexpr ((M & 1) == 0) st.dv[db] = mfma32(abuf[M % NBUF], st.pb[h], st.dv[db]);
+      else st.dk[db] = mfma32(abuf[M % NBUF], st.dsb[h], st.dk[db]);
+    } else {
+      constexpr int j = M - N_AC, ks = j / 2;
+      const f32x16 zero = {0};
+      if constexpr ((j & 1) == 0) st.s = mfma32(abuf[M % NBUF], st.kreg[ks], ks == 0 ? zero : st.s);
+      else st.dp = mfma32(abuf[M % NBUF], vb[ks & 1], ks == 0 ? zero : st.dp);
+    }
+  }
+  template <int M>
+  SP_DEV void step() {
+    if constexpr (M < N) {
+      reads<M + LOOK>();
+      SP_FENCE();
+      mfma<M>();
+      SP_FENCE();
+      step<M + 1>();
+    }
+  }
+  template <int M>
+  SP_DEV void prologue() {
+    if constexpr (M < LOOK) { reads<M>(); prologue<M + 1>(); }
+  }
+  SP_DEV void run() {
+    SP_FENCE();
+    prologue<0>();
+    SP_FENCE();
+    step<0>();
+  }
+};
+
+// P = exp2(c S - lse2) on visible pairs, dS = P (dP - delta); element i of a lane is query row
+// 8*(i/4) + 4g + i%4 of the tile, the lane's column is its key.  `hook(i)`, i = 0..3, is called at four
+// points spread over the phase (asynchronous tile copies ride there).
+template <int D, class H>
+SP_DEV void dkdv_vector_phase(DkdvState<D>& st, const float* stat, float c, bool need_mask, int rmin_rel, int rmax_rel,
+                              int g, H&& hook) {
+  if (need_mask) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int r = 8 * (i >> 2) + 4 * g + (i & 3);
-      s[i] = ((r >= rmin_rel) & (r < rmax_rel)) ? s[i] : -INFINITY;      // exp2(-inf) = 0
+      st.s[i] = ((r >= rmin_rel) & (r < rmax_rel)) ? st.s[i] : -INFINITY;      // exp2(-inf) = 0
     }
   }
 #pragma unroll
   for (int i4 = 0; i4 < 4; ++i4) {
-    const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_t + qb * 32 + 8 * i4 + 4 * g);
-    const f32x4 d4 = *reinterpret_cast<const f32x4*>(del_t + qb * 32 + 8 * i4 + 4 * g);
+    hook(i4);
+    const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + 8 * i4 + 4 * g);
+    const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat + 32 + 8 * i4 + 4 * g);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int i = 4 * i4 + j;
-      const float p = exp2_fast(__builtin_fmaf(s[i], c, -l4[j]));
-      s[i] = p;
-      dp[i] = p * (dp[i] - d4[j]);
+      const float p = exp2_fast(__builtin_fmaf(st.s[i], c, -l4[j]));
+      st.s[i] = p;
+      st.dp[i] = p * (st.dp[i] - d4[j]);
+    }
+    if (i4 & 1) {
+      st.pb[i4 >> 1] = pack8(st.s, 8 * (i4 >> 1));
+      st.dsb[i4 >> 1] = pack8(st.dp, 8 * (i4 >> 1));
+      // pin: without a use here the optimiser sinks this arithmetic past the phase barrier
+      asm volatile("" : "+v"(st.pb[i4 >> 1]), "+v"(st.dsb[i4 >> 1]));
     }
   }
 }
 
-// Transposed operands of one 16-row half block for dV^T += dO^T P and dK^T += Q^T dS.
-template <int D>
-struct AccOps { bf16x8 dot[D / 32], qt[D / 32]; };
-
-template <int D, int TILE_BYTES>
-SP_DEV void dkdv_load_acc(const char* smem, const TrOffsets<D>& lo, int half_off, AccOps<D>& o) {
-#pragma unroll
-  for (int db = 0; db < D / 32; ++db) {
-    o.dot[db] = lds_tr<D>(smem, lo, db, TILE_BYTES + half_off);
-    o.qt[db] = lds_tr<D>(smem, lo, db, half_off);
-  }
-}
-template <int D>
-SP_DEV void dkdv_accumulate(const AccOps<D>& o, bf16x8 pb, bf16x8 dsb, f32x16 (&dk)[D / 32], f32x16 (&dv)[D / 32]) {
-#pragma unroll
-  for (int db = 0; db < D / 32; ++db) {
-    dv[db] = mfma32(o.dot[db], pb, dv[db]);
-    dk[db] = mfma32(o.qt[db], dsb, dk[db]);
-  }
-}
-
-// The global->LDS traffic of the tile two steps ahead.  It is staged through registers (global
-// loads early in a tile, LDS writes at its end): the compiler must assume that an asynchronous
-// global->LDS copy aliases every later LDS read and would make the wave wait for it on the spot.
-struct DkdvDma {
-  const bf16_t* q;         // head base of Q
-  const bf16_t* dout;      // head base of dO
-  const float* lse2;       // head base of the row statistics
-  const float* delta;
-  int64_t q_stride_s, do_stride_s;
-  int row0, row_last;      // first row of the tile, last valid row of the slice
-  char* dst;               // LDS: Q tile, dO tile behind it
-  float* dst_stats;        // LDS: lse2[BMQ], delta[BMQ]
-};
-template <int D, int BMQ, int T>
-struct DkdvStage {
-  static constexpr int NC = D / 8, PASSES = BMQ * NC / T, PARTS = 4;
-  static constexpr int part_of(int n) { return PASSES >= PARTS ? n % PARTS : n * (PARTS / PASSES); }
-  u32x4 q[PASSES], o[PASSES];
-  float stat;
-  // Part P of the global loads of one tile.  The L1 path moves 64 bytes per clock for the whole CU
-  // and a wave stalls at issue while it is busy, so the parts are spread over the pipeline steps.
-  template <int P>
-  SP_DEV void load_part(const DkdvDma& j, int tid) {
-#pragma unroll
-    for (int n = 0; n < PASSES; ++n) {
-      if (part_of(n) != P) continue;
-      const int id = tid + n * T;
-      const int r = id / NC, c = id % NC;
-      int64_t gr = j.row0 + r;
-      gr = gr < j.row_last ? gr : j.row_last;
-      q[n] = *reinterpret_cast<const u32x4*>(j.q + gr * j.q_stride_s + c * 8);
-      o[n] = *reinterpret_cast<const u32x4*>(j.dout + gr * j.do_stride_s + c * 8);
-    }
-    if (P == PARTS - 1 && tid < 2 * BMQ) {     // threads [0,BMQ): lse2 rows, [BMQ,2BMQ): delta rows
-      int r = j.row0 + (tid & (BMQ - 1));
-      r = r < j.row_last ? r : j.row_last;
-      stat = (tid < BMQ ? j.lse2 : j.delta)[r];
-    }
-  }
-  SP_DEV void load(const DkdvDma& j, int tid) {
-    load_part<0>(j, tid); load_part<1>(j, tid); load_part<2>(j, tid); load_part<3>(j, tid);
-  }
-  SP_DEV void store(char* dst, float* dst_stats, int tid) const {
-#pragma unroll
-    for (int n = 0; n < PASSES; ++n) {
-      const int id = tid + n * T;
-      const int r = id / NC, c = id % NC;
-      *reinterpret_cast<u32x4*>(dst + tile_off<D>(r, c)) = q[n];
-      *reinterpret_cast<u32x4*>(dst + BMQ * D * 2 + tile_off<D>(r, c)) = o[n];
-    }
-    if (tid < 2 * BMQ) dst_stats[tid] = stat;
-  }
-};
-
-// One pipeline step: consumes the scores (s, dp) of block (tile t, block qb), produces the scores of
-// the following block into (s_n, dp_n) from `ops`, then refills `ops` with the block after that.
-//   cur: tile t (transposed reads), nxt_blk_off: where block j+1 .. the refill reads from (row-packed,
-//   through lo_rp which already points at the right tile).
-template <int D, int BMQ, int T, bool MASK, int QB_IDX>
-SP_DEV void dkdv_step(const char* smem, const TrOffsets<D>& lo_tr, const RpOffsets<D>& lo_rp, int refill_off,
-                      DkdvStage<D, BMQ, T>& stage, const DkdvDma& dma, char* store_dst, float* store_stats, int tid,
-                      const float* lse_t, const float* del_t, int g, float c, int rmin_tile, int rows_left,
-                      const bf16x8 (&kreg)[D / 16], const bf16x8 (&vreg)[D / 16], ScoreOps<D>& ops,
-                      f32x16& s, f32x16& dp, f32x16& s_n, f32x16& dp_n, f32x16 (&dk)[D / 32], f32x16 (&dv)[D / 32]) {
-  constexpr int TILE_BYTES = BMQ * D * 2, BLK = 32 * D * 2, HALF = 16 * D * 2;
-  constexpr int NM = 2 * (D / 16);
-  AccOps<D> acc0, acc1;
-  constexpr int qb = QB_IDX;
-  SP_FENCE();
-  // ---- region X
-  if (QB_IDX == 1) { stage.template load_part<0>(dma, tid); stage.template load_part<1>(dma, tid); }
-  dkdv_scores<D>(ops, kreg, vreg, s_n, dp_n);
-  int rmin_rel = 0, rmax_rel = 32;
-  if (MASK) {
-    const int rmin = rmin_tile - qb * 32, left = rows_left - qb * 32;
-    rmin_rel = rmin < 0 ? 0 : (rmin > 32 ? 32 : rmin);
-    rmax_rel = left < 0 ? 0 : (left > 32 ? 32 : left);
-  }
-  dkdv_softmax<MASK>(s, dp, lse_t, del_t, qb, g, c, rmin_rel, rmax_rel);
-  const bf16x8 pb0 = pack8(s, 0), pb1 = pack8(s, 8);
-  const bf16x8 ds0 = pack8(dp, 0), ds1 = pack8(dp, 8);
-  dkdv_load_acc<D, TILE_BYTES>(smem, lo_tr, qb * BLK, acc0);
-  dkdv_load_acc<D, TILE_BYTES>(smem, lo_tr, qb * BLK + HALF, acc1);
-#pragma unroll
-  for (int i = 0; i < NM; ++i) {
-    __builtin_amdgcn_sched_group_barrier(SP_SG_MFMA, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(SP_SG_VALU, 7, 0);
-    __builtin_amdgcn_sched_group_barrier(SP_SG_DSRD, 3, 0);
-  }
-  SP_FENCE();
-  // ---- region Y
-  if (QB_IDX == 1) { stage.template load_part<2>(dma, tid); stage.template load_part<3>(dma, tid); }
-  if (QB_IDX == 0) stage.store(store_dst, store_stats, tid);
-  dkdv_accumulate<D>(acc0, pb0, ds0, dk, dv);
-  dkdv_accumulate<D>(acc1, pb1, ds1, dk, dv);
-  dkdv_load_ops<D, TILE_BYTES>(smem, lo_rp, refill_off, ops);
-#pragma unroll
-  for (int i = 0; i < NM; ++i) {
-    __builtin_amdgcn_sched_group_barrier(SP_SG_MFMA, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(SP_SG_DSRD, 1, 0);
-  }
-  SP_FENCE();
-}
-
-template <int D, int NW, int BMQ>
+template <int D, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a) {
-  constexpr int BNK = NW * 32, KS = D / 16, DB = D / 32, T = NW * 64;
-  constexpr int TILE_BYTES = BMQ * D * 2, BLK = 32 * D * 2;
-  constexpr int BUF_BYTES = 2 * TILE_BYTES;                    // Q tile, dO tile
-  constexpr int NBUF = 3;
-  static_assert(BMQ == 64, "the pipeline below is written for two 32-row blocks per tile");
-  static_assert(2 * BMQ <= T, "one thread per staged row statistic");
+  static_assert(NW == 8, "two groups of four waves");
+  using L = DkdvLds<D, NW>;
+  constexpr int BNK = NW * 32, BMQ = L::BMQ, KS = D / 16, DB = D / 32, T = NW * 64, GT = T / 2;
+  constexpr int TILE_BYTES = L::TILE_BYTES, SLOTS = L::SLOTS;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  float* stats = reinterpret_cast<float*>(smem + NBUF * BUF_BYTES);   // [NBUF][lse2[BMQ], delta[BMQ]]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ql = lane & 31;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);      // known uniform to the compiler
+  const bool group_b = wave_u >= NW / 2;
+  const int gtid = tid & (GT - 1);
   const int hk = blockIdx.y, b = blockIdx.z;
   const int64_t tile_key0 = a.kv_begin + (int64_t)blockIdx.x * BNK;
-  const int64_t wkey0 = tile_key0 + wave * 32;
-  const int64_t mykey = wkey0 + ql;
+  const int64_t mykey = tile_key0 + wave_u * 32 + ql;
   const int64_t mykey_c = mykey < a.kv_end ? mykey : a.kv_end - 1;
 
-  // K, V as B operands: column = my key, k-slots = head_dim 16*ks + 8g ..
-  bf16x8 kreg[KS], vreg[KS];
+  DkdvState<D> st;
   {
-    const int64_t off = (int64_t)b * a.kv_stride_b + mykey_c * a.kv_stride_s + (int64_t)hk * a.kv_stride_h;
+    // K as B operand: column = my key, k-slots = head_dim 16*ks + 8g ..
+    const bf16_t* kp = a.k + (int64_t)b * a.kv_stride_b + mykey_c * a.kv_stride_s + (int64_t)hk * a.kv_stride_h;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      kreg[ks] = *reinterpret_cast<const bf16x8*>(a.k + off + 16 * ks + 8 * g);
-      vreg[ks] = *reinterpret_cast<const bf16x8*>(a.v + off + 16 * ks + 8 * g);
-    }
+    for (int ks = 0; ks < KS; ++ks) st.kreg[ks] = *reinterpret_cast<const bf16x8*>(kp + 16 * ks + 8 * g);
   }
-  f32x16 dk[DB], dv[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { dk[db][i] = 0.f; dv[db][i] = 0.f; }
+    for (int i = 0; i < 16; ++i) { st.dk[db][i] = 0.f; st.dv[db][i] = 0.f; }
 
   // Query tiles that can see this key tile: [qt0, nqt).  Tiles that need a mask (they straddle the
   // causal diagonal of this key tile, or hold rows past s_q) are walked first, for every head of the
-  // group, then the unmasked rest; the order is fixed, so the sums are reproducible.
+  // group, then the unmasked rest.
   const int nqt = (a.s_q + BMQ - 1) / BMQ;
   int qt0 = 0, qtm = 0;                                      // masked: [qt0, qtm) (+ a partial last tile)
   if (a.causal && tile_key0 > a.q_offset) {
@@ -622,120 +563,142 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
   const int nu = (nqt - qtm) - (partial_last ? 1 : 0);       // unmasked tiles per head
   const int total_m = nm * a.group, total = (nm + nu) * a.group;
   const float c = a.scale_log2e;
-  // first row (absolute, within the slice) that sees this lane's key
+  // first row (within the slice) that sees this lane's key
   const int64_t rmin_abs = a.causal ? mykey - a.q_offset : 0;
 
-  // sequence index -> (head of the group, query tile)
-  auto locate = [&](int seq, int& hh, int& qt) {
-    if (seq < total_m) {
-      hh = seq / nm;
-      const int r = seq % nm;
-      qt = (r < qtm - qt0) ? qt0 + r : nqt - 1;
-    } else {
-      const int u = seq - total_m;
-      hh = u / nu;
-      qt = qtm + u % nu;
-    }
-  };
-
-  auto make_dma = [&](int seq, int buf) {
-    int hh, qt;
-    locate(seq, hh, qt);
-    const int h = hk * a.group + hh;
-    DkdvDma j;
-    j.q = a.q + (int64_t)b * a.q_stride_b + (int64_t)h * a.q_stride_h;
-    j.dout = a.d_out + (int64_t)b * a.do_stride_b + (int64_t)h * a.do_stride_h;
-    j.lse2 = a.lse2 + ((int64_t)b * a.n_q_heads + h) * a.s_q;
-    j.delta = a.delta + ((int64_t)b * a.n_q_heads + h) * a.s_q;
-    j.q_stride_s = a.q_stride_s;
-    j.do_stride_s = a.do_stride_s;
-    j.row0 = qt * BMQ;
-    j.row_last = a.s_q - 1;
-    j.dst = smem + buf * BUF_BYTES;
-    j.dst_stats = stats + buf * 2 * BMQ;
-    return j;
-  };
   if (total > 0) {
-    // ---- prologue: tiles 0 and 1 resident, scores of block 0 computed, operands of block 1 loaded
-    DkdvStage<D, BMQ, T> stage;
-    // tiles 0 and 1 go to LDS, tile 2 waits in the staging registers (tile indices past the end of
-    // the stream are clamped: the last tile is fetched again and nobody reads it)
-    for (int t = 0; t < 3; ++t) {
-      const int tt = t < total ? t : total - 1;
-      const DkdvDma j = make_dma(tt, t);
-      stage.load(j, tid);
-      if (t < 2) stage.store(smem + t * BUF_BYTES, stats + t * 2 * BMQ, tid);
+    // sequence index -> (query head, first row of the tile)
+    struct TileRef { int h, row0; };
+    auto locate = [&](int seq) {
+      int hh, qt;
+      if (seq < total_m) {
+        hh = seq / nm;
+        const int r = seq % nm;
+        qt = (r < qtm - qt0) ? qt0 + r : nqt - 1;
+      } else {
+        const int u = seq - total_m;
+        hh = u / nu;
+        qt = qtm + u % nu;
+      }
+      TileRef t;
+      t.h = hk * a.group + hh;
+      t.row0 = qt * BMQ;
+      return t;
+    };
+    TileDma<D, BMQ, GT> dma;
+    constexpr int PASSES = TileDma<D, BMQ, GT>::PASSES;
+    static_assert(PASSES <= 3, "copy instructions of a tile fit the hooks of a vector phase");
+    dma.init(gtid);
+    struct CopyJob { const bf16_t* src; char* dst; uint32_t row_bytes; int rows; const float* stat_src; unsigned stat_dst; };
+    // tile t of Q (group A, with the row statistics) or dO (group B); past the end of the stream the last tile again
+    auto make_copy = [&](bool is_q, int t) {
+      const TileRef tr = locate(t < total ? t : total - 1);
+      const int slot = t % SLOTS;
+      CopyJob j;
+      if (is_q) {
+        j.src = a.q + (int64_t)b * a.q_stride_b + (int64_t)tr.h * a.q_stride_h + (int64_t)tr.row0 * a.q_stride_s;
+        j.row_bytes = (uint32_t)a.q_stride_s * 2;
+      } else {
+        j.src = a.d_out + (int64_t)b * a.do_stride_b + (int64_t)tr.h * a.do_stride_h + (int64_t)tr.row0 * a.do_stride_s;
+        j.row_bytes = (uint32_t)a.do_stride_s * 2;
+      }
+      j.dst = smem + (is_q ? L::Q_BASE : L::DO_BASE) + slot * TILE_BYTES;
+      j.rows = a.s_q - tr.row0;
+      // lanes 0..31: lse2 of rows row0 .. row0+31, lanes 32..63: delta of the same rows (clamped to the slice)
+      int r = tr.row0 + ql;
+      r = r < a.s_q ? r : a.s_q - 1;
+      j.stat_src = (g ? a.delta : a.lse2) + ((int64_t)b * a.n_q_heads + tr.h) * a.s_q + r;
+      j.stat_dst = __builtin_amdgcn_readfirstlane((unsigned)reinterpret_cast<uintptr_t>(
+          (__attribute__((address_space(3))) char*)(smem + L::STAT_BASE + slot * L::STAT_BYTES)));
+      return j;
+    };
+    auto copy_pass = [&](const CopyJob& j, int n) { dma.issue(j.dst, j.src, j.row_bytes, j.rows, gtid, n); };
+    // every wave of group A writes the same 64 statistics (no branch in the phase: identical data)
+    auto copy_part = [&](const CopyJob& j, bool with_stats, int part) {
+      if (part < PASSES) copy_pass(j, part);
+      if (part == 3 && with_stats) dma4(j.stat_src, j.stat_dst);
+    };
+    auto copy_all = [&](const CopyJob& j, bool with_stats) {
+      for (int part = 0; part < 4; ++part) copy_part(j, with_stats, part);
+    };
+
+    // prologue: V rows of the workgroup (all threads), Q(0), Q(1) + statistics (group A), dO(0), dO(1) (group B)
+    {
+      TileDma<D, BNK, T> dma_v;
+      dma_v.init(tid);
+      const bf16_t* vbase = a.v + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h + tile_key0 * a.kv_stride_s;
+      const int64_t avail = a.kv_end - tile_key0;
+      for (int n = 0; n < TileDma<D, BNK, T>::PASSES; ++n)
+        dma_v.issue(smem + L::V_BASE, vbase, (uint32_t)a.kv_stride_s * 2, avail > BNK ? BNK : (int)avail, tid, n);
     }
+    const bool copies_q = !group_b;
+    copy_all(make_copy(copies_q, 0), copies_q);
+    copy_all(make_copy(copies_q, 1), copies_q);
+    wait_async();
+    TrBase<D> lo_qt;         // Q(u-1), transposed
+    RpBase<D> lo_q, lo_v;    // Q(u) and this wave's V rows, row-packed
+    lo_qt.init(lane, L::Q_BASE + (SLOTS - 1) * TILE_BYTES);     // "Q(-1)": never read
+    lo_q.init(lane, L::Q_BASE);
+    lo_v.init(lane, L::V_BASE + wave_u * 32 * D * 2);
     __syncthreads();
 
-    TrOffsets<D> lo_tr;      // tile being consumed
-    RpOffsets<D> lo_rp;      // tile the score operands are read from
-    lo_tr.init(lane, 0);
-    lo_rp.init(lane, 0);
-    ScoreOps<D> ops;
-    f32x16 sA, dpA, sB, dpB;
-    dkdv_load_ops<D, TILE_BYTES>(smem, lo_rp, 0, ops);
-    dkdv_scores<D>(ops, kreg, vreg, sA, dpA);
-    dkdv_load_ops<D, TILE_BYTES>(smem, lo_rp, BLK, ops);
-    lo_rp.add(BUF_BYTES);    // from now on: one tile ahead of lo_tr
-
-    int cur = 0;             // ring slot of the tile being consumed
+    int slot = 0;            // ring slot of tile u
+    auto advance = [&]() {
+      lo_q.add(slot == SLOTS - 1 ? -(SLOTS - 1) * TILE_BYTES : TILE_BYTES);
+      lo_qt.add(slot == 0 ? -(SLOTS - 1) * TILE_BYTES : TILE_BYTES);      // Q(u-1) sits in slot - 1
+      slot = (slot == SLOTS - 1) ? 0 : slot + 1;
+    };
+    auto vector_phase = [&](int u, const CopyJob& j) {
+      const bool need_mask = u < total_m;
+      int rmin_rel = 0, rmax_rel = 32;
+      if (need_mask) {
+        const TileRef tr = locate(u);
+        const int64_t rl = rmin_abs - tr.row0;
+        rmin_rel = rl < 0 ? 0 : (rl > 32 ? 32 : (int)rl);
+        const int left = a.s_q - tr.row0;
+        rmax_rel = left > 32 ? 32 : left;
+      }
+      const float* stat = reinterpret_cast<const float*>(smem + L::STAT_BASE + (u % SLOTS) * L::STAT_BYTES);
+      dkdv_vector_phase<D>(st, stat, c, need_mask, rmin_rel, rmax_rel, g, [&](int part) { copy_part(j, copies_q, part); });
+    };
 #ifdef SLIMPIPE_TRACE
-    long long tr_wait = 0, tr_issue = 0, tr_s0 = 0, tr_s1 = 0, tr_t0 = clock64(), tr_w0 = wall_clock64();
+    long long tr_v = 0, tr_b1 = 0, tr_m = 0, tr_w = 0, tr_b2 = 0, tr_t0 = clock64(), tr_w0 = wall_clock64(), tr_last = clock64();
 #define TR_MARK(var) { long long _n = clock64(); var += _n - tr_last; tr_last = _n; }
 #else
 #define TR_MARK(var)
 #endif
-    auto tile_body = [&](int seq, auto mask_tag) {
-      constexpr bool MASK = decltype(mask_tag)::value;
-#ifdef SLIMPIPE_TRACE
-      long long tr_last = clock64();
-#endif
-      // tile seq+1 is written (it was stored one tile ago), every wave is done with tile seq-1
-      if (seq > 0) __syncthreads();
-      TR_MARK(tr_wait)
-      // the tile two steps ahead goes into the slot tile seq-1 just left; past the end of the stream
-      // the last tile is fetched again (nobody reads it) so that the steps stay branch-free
-      const int free_slot = cur == 0 ? NBUF - 1 : cur - 1;
-      // tile seq+2, loaded during the second step of tile seq-1, goes into the slot that tile just left
-      // (written during the first step below); the loads of tile seq+3 are issued in the second step
-      const DkdvDma dma = make_dma(seq + 3 < total ? seq + 3 : total - 1, 0);
-      TR_MARK(tr_issue)
-      const float* lse_t = stats + cur * 2 * BMQ;
-      int rmin_tile = 0, rows_left = BMQ;
-      if (MASK) {
-        int hh, qt;
-        locate(seq, hh, qt);
-        const int row0 = qt * BMQ;
-        const int64_t rl = rmin_abs - row0;
-        rmin_tile = rl < 0 ? 0 : (rl > BMQ ? BMQ : (int)rl);
-        rows_left = a.s_q - row0;
-      }
-      // block 0 of the tile: next scores = block 1 of this tile (ops already hold it);
-      // refill ops with block 0 of the next tile
-      dkdv_step<D, BMQ, T, MASK, 0>(smem, lo_tr, lo_rp, 0, stage, dma, smem + free_slot * BUF_BYTES, stats + free_slot * 2 * BMQ, tid, lse_t, lse_t + BMQ, g, c,
-                                 rmin_tile, rows_left, kreg, vreg, ops, sA, dpA, sB, dpB, dk, dv);
-      TR_MARK(tr_s0)
-      // block 1: next scores = block 0 of the next tile; refill with block 1 of the next tile
-      dkdv_step<D, BMQ, T, MASK, 1>(smem, lo_tr, lo_rp, BLK, stage, dma, smem + free_slot * BUF_BYTES, stats + free_slot * 2 * BMQ, tid, lse_t, lse_t + BMQ, g, c,
-                                 rmin_tile, rows_left, kreg, vreg, ops, sB, dpB, sA, dpA, dk, dv);
-      TR_MARK(tr_s1)
-      // advance the ring
-      const int step_tr = (cur == NBUF - 1) ? -(NBUF - 1) * BUF_BYTES : BUF_BYTES;
-      const int step_rp = (cur == NBUF - 2) ? -(NBUF - 1) * BUF_BYTES : BUF_BYTES;
-      lo_tr.add(step_tr);
-      lo_rp.add(step_rp);
-      cur = (cur == NBUF - 1) ? 0 : cur + 1;
-    };
-
-    int seq = 0;
-    for (; seq < total_m; ++seq) tile_body(seq, std::true_type{});     // masked tiles
-    for (; seq < total; ++seq) tile_body(seq, std::false_type{});      // unmasked tiles: the bulk
+    // Both groups run the same code; group B starts one phase (one barrier) later and group A idles
+    // one phase at the end.
+    if (group_b) phase_end();
+    { DkdvMatrixPhase<D, NW, false, true, 2> ph{smem, lo_qt, lo_q, lo_v, st}; ph.run(); }     // scores of tile 0
+    advance();
+    wait_async();
+    phase_end();
+    TR_MARK(tr_b2)
+    for (int u = 0; u + 1 < total; ++u) {
+      vector_phase(u, make_copy(copies_q, u + 2));       // tile u+2 rides along
+      TR_MARK(tr_v)
+      phase_end();
+      TR_MARK(tr_b1)
+      { DkdvMatrixPhase<D, NW, true, true, 2> ph{smem, lo_qt, lo_q, lo_v, st}; ph.run(); }    // sums of tile u, scores of tile u+1
+      advance();
+      TR_MARK(tr_m)
+      wait_async();                                      // the copies of the vector phase before have landed
+      TR_MARK(tr_w)
+      phase_end();
+      TR_MARK(tr_b2)
+    }
+    vector_phase(total - 1, make_copy(copies_q, total + 1));
+    phase_end();
+    { DkdvMatrixPhase<D, NW, true, false, 2> ph{smem, lo_qt, lo_q, lo_v, st}; ph.run(); }     // sums of the last tile
+    wait_async();
+    phase_end();
+    if (!group_b) phase_end();
 #ifdef SLIMPIPE_TRACE
     if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {
       long long* dbg = reinterpret_cast<long long*>(a.lse2 + (int64_t)a.n_q_heads * a.s_q);   // behind the workspace proper
-      dbg[0] = tr_wait; dbg[1] = tr_issue; dbg[2] = tr_s0; dbg[3] = tr_s1;
-      dbg[4] = clock64() - tr_t0; dbg[5] = wall_clock64() - tr_w0; dbg[6] = total;
+      dbg[0] = tr_v; dbg[1] = tr_b1; dbg[2] = tr_m; dbg[3] = tr_w; dbg[4] = tr_b2;
+      dbg[5] = clock64() - tr_t0; dbg[6] = wall_clock64() - tr_w0; dbg[7] = total;
     }
 #endif
   }
@@ -747,9 +710,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
         const int d = 32 * db + 8 * i4 + 4 * g;
-        f32x4 k4 = {dk[db][4 * i4] * a.scale, dk[db][4 * i4 + 1] * a.scale, dk[db][4 * i4 + 2] * a.scale,
-                    dk[db][4 * i4 + 3] * a.scale};
-        f32x4 v4 = {dv[db][4 * i4], dv[db][4 * i4 + 1], dv[db][4 * i4 + 2], dv[db][4 * i4 + 3]};
+        f32x4 k4 = {st.dk[db][4 * i4] * a.scale, st.dk[db][4 * i4 + 1] * a.scale, st.dk[db][4 * i4 + 2] * a.scale,
+                    st.dk[db][4 * i4 + 3] * a.scale};
+        f32x4 v4 = {st.dv[db][4 * i4], st.dv[db][4 * i4 + 1], st.dv[db][4 * i4 + 2], st.dv[db][4 * i4 + 3]};
         f32x4* kd = reinterpret_cast<f32x4*>(a.dk_acc + base + d);
         f32x4* vd = reinterpret_cast<f32x4*>(a.dv_acc + base + d);
         if (a.dkv_accumulate) { k4 += *kd; v4 += *vd; }
@@ -759,13 +722,13 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
   }
 }
 
-template <int D, int NW, int BMQ>
+template <int D, int NW>
 static hipError_t launch_dkdv_t(const BwdArgs& a, int batch, hipStream_t st) {
   constexpr int BNK = NW * 32;
-  const size_t smem = (size_t)3 * (2 * BMQ * D * 2) + 3 * 2 * BMQ * 4;
+  const size_t smem = DkdvLds<D, NW>::TOTAL;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dkdv_kernel<D, NW, BMQ>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dkdv_kernel<D, NW>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -773,13 +736,13 @@ static hipError_t launch_dkdv_t(const BwdArgs& a, int batch, hipStream_t st) {
   const int64_t nkeys = a.kv_end - a.kv_begin;
   if (nkeys <= 0) return hipSuccess;
   dim3 grid((unsigned)((nkeys + BNK - 1) / BNK), a.n_kv_heads, batch), block(NW * 64);
-  hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, NW, BMQ>), grid, block, smem, st, a);
+  hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, NW>), grid, block, smem, st, a);
   return hipGetLastError();
 }
 
 hipError_t launch_bwd_dkdv(const BwdArgs& a, int batch, int head_dim, hipStream_t st) {
-  if (head_dim == 128) return launch_dkdv_t<128, 4, 64>(a, batch, st);
-  return launch_dkdv_t<64, 4, 64>(a, batch, st);
+  if (head_dim == 128) return launch_dkdv_t<128, 8>(a, batch, st);
+  return launch_dkdv_t<64, 8>(a, batch, st);
 }
 
 }  // namespace slimpipe

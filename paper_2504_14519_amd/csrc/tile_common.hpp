@@ -233,6 +233,11 @@ SP_DEV void dma16(const void* src, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :: "v"(src), "s"(lds_base) : "memory", "m0");
 }
+// one dword per lane: lane i lands at lds_base + 4*i
+SP_DEV void dma4(const void* src, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+               :: "v"(src), "s"(lds_base) : "memory", "m0");
+}
 template <int D, int ROWS, int THREADS>
 SP_DEV void tile_load_async(char* tile, const bf16_t* base, int64_t row_stride, int64_t row0, int64_t row_last, int tid) {
   constexpr int NC = D / 8;
