@@ -244,18 +244,20 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
     static_assert(PASSES <= 4, "one copy instruction per hook of the vector phase");
     dma.init(gtid);
     const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2;
-    struct CopyJob { const bf16_t* src; char* dst; int rows; };
+    const unsigned smem_lds = lds_addr(smem);
+    const int gwave_u = wave_u & (NW / 2 - 1);
+    struct CopyJob { const bf16_t* src; unsigned dst; int rows; };
     // tile t of K (slot t % KSLOTS) or V (slot t % VSLOTS); past the end the last tile is copied again
     auto make_copy = [&](bool is_k, int t) {
       const int64_t key0 = key0_of(t < nt ? t : nt - 1);
       const int64_t avail = a.kv_capacity - key0;
       CopyJob j;
       j.src = (is_k ? kbase : vbase) + key0 * a.kv_stride_s;
-      j.dst = smem + (is_k ? K_BASE + (t % KSLOTS) * TILE_BYTES : V_BASE + (t % VSLOTS) * TILE_BYTES);
+      j.dst = smem_lds + (is_k ? K_BASE + (t % KSLOTS) * TILE_BYTES : V_BASE + (t % VSLOTS) * TILE_BYTES);
       j.rows = avail > BN ? BN : (int)avail;
       return j;
     };
-    auto copy_pass = [&](const CopyJob& j, int n) { dma.issue(j.dst, j.src, row_bytes, j.rows, gtid, n); };
+    auto copy_pass = [&](const CopyJob& j, int n) { dma.issue(j.dst, j.src, row_bytes, j.rows, gwave_u, n); };
     auto copy_all = [&](const CopyJob& j) {
       for (int n = 0; n < PASSES; ++n) copy_pass(j, n);
     };
@@ -275,7 +277,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
       dma_do.init(tid);
       const bf16_t* dobase = a.d_out + (int64_t)b * a.do_stride_b + (int64_t)m0 * a.do_stride_s + (int64_t)h * a.do_stride_h;
       for (int n = 0; n < TileDma<D, BM, T>::PASSES; ++n)
-        dma_do.issue(smem + DO_BASE, dobase, (uint32_t)a.do_stride_s * 2, a.s_q - m0, tid, n);
+        dma_do.issue(smem_lds + DO_BASE, dobase, (uint32_t)a.do_stride_s * 2, a.s_q - m0, wave_u, n);
     }
     if (!group_b) { copy_all(make_copy(true, 0)); copy_all(make_copy(true, 1)); }
     else { copy_all(make_copy(false, 0)); copy_all(make_copy(false, 1)); }
@@ -494,24 +496,34 @@ SP_DEV void dkdv_vector_phase(DkdvState<D>& st, const float* stat, float c, bool
       st.s[i] = ((r >= rmin_rel) & (r < rmax_rel)) ? st.s[i] : -INFINITY;      // exp2(-inf) = 0
     }
   }
+  // all row statistics first: the copy instructions in the hooks are compiler barriers for memory
+  // operations, and an LDS read placed after one would be waited for on the spot
+  f32x4 l4[4], d4[4];
 #pragma unroll
   for (int i4 = 0; i4 < 4; ++i4) {
-    hook(i4);
-    const f32x4 l4 = *reinterpret_cast<const f32x4*>(stat + 8 * i4 + 4 * g);
-    const f32x4 d4 = *reinterpret_cast<const f32x4*>(stat + 32 + 8 * i4 + 4 * g);
+    l4[i4] = *reinterpret_cast<const f32x4*>(stat + 8 * i4 + 4 * g);
+    d4[i4] = *reinterpret_cast<const f32x4*>(stat + 32 + 8 * i4 + 4 * g);
+  }
+  // stage by stage over all 16 elements, so that neighbouring instructions do not depend on each other
+  hook(0);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int i = 4 * i4 + j;
-      const float p = exp2_fast(__builtin_fmaf(st.s[i], c, -l4[j]));
-      st.s[i] = p;
-      st.dp[i] = p * (st.dp[i] - d4[j]);
-    }
-    if (i4 & 1) {
-      st.pb[i4 >> 1] = pack8(st.s, 8 * (i4 >> 1));
-      st.dsb[i4 >> 1] = pack8(st.dp, 8 * (i4 >> 1));
-      // pin: without a use here the optimiser sinks this arithmetic past the phase barrier
-      asm volatile("" : "+v"(st.pb[i4 >> 1]), "+v"(st.dsb[i4 >> 1]));
-    }
+  for (int i = 0; i < 16; ++i) st.s[i] = __builtin_fmaf(st.s[i], c, -l4[i >> 2][i & 3]);
+  hook(1);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    st.s[i] = exp2_fast(st.s[i]);
+    st.dp[i] -= d4[i >> 2][i & 3];
+  }
+  hook(2);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) st.dp[i] *= st.s[i];
+  hook(3);
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    st.pb[h] = pack8(st.s, 8 * h);
+    st.dsb[h] = pack8(st.dp, 8 * h);
+    // pin: without a use here the optimiser sinks this arithmetic past the phase barrier
+    asm volatile("" : "+v"(st.pb[h]), "+v"(st.dsb[h]));
   }
 }
 
@@ -567,52 +579,88 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
   const int64_t rmin_abs = a.causal ? mykey - a.q_offset : 0;
 
   if (total > 0) {
-    // sequence index -> (query head, first row of the tile)
-    struct TileRef { int h, row0; };
-    auto locate = [&](int seq) {
-      int hh, qt;
-      if (seq < total_m) {
-        hh = seq / nm;
-        const int r = seq % nm;
-        qt = (r < qtm - qt0) ? qt0 + r : nqt - 1;
-      } else {
-        const int u = seq - total_m;
-        hh = u / nu;
-        qt = qtm + u % nu;
-      }
-      TileRef t;
-      t.h = hk * a.group + hh;
-      t.row0 = qt * BMQ;
-      return t;
+    // Position in the stream of query tiles: masked tiles of head 0, 1, .. of the group, then the unmasked
+    // tiles of head 0, 1, ..  Stepping it is a few scalar additions when the next tile follows in the
+    // same head (no division, no 64-bit product: a wave issues in order and a chain of scalar
+    // operations holds up the vector work behind it); it stays on the last tile once it is there.
+    struct Cursor {
+      int seq, hh, r, row0;
+      bool unmasked;
     };
+    auto cursor_row0 = [&](const Cursor& cur) {
+      const int qt = cur.unmasked ? qtm + cur.r : (cur.r < qtm - qt0 ? qt0 + cur.r : nqt - 1);
+      return qt * BMQ;
+    };
+    auto cursor_begin = [&]() {
+      Cursor cur;
+      cur.seq = 0; cur.hh = 0; cur.r = 0;
+      cur.unmasked = nm == 0;
+      cur.row0 = cursor_row0(cur);
+      return cur;
+    };
+    // -> true when the new tile is the one right after the old one in the same head
+    auto cursor_next = [&](Cursor& cur) {
+      if (cur.seq + 1 >= total) return false;
+      ++cur.seq;
+      ++cur.r;
+      if (cur.r == (cur.unmasked ? nu : nm)) {
+        cur.r = 0;
+        ++cur.hh;
+        if (cur.hh == a.group) { cur.hh = 0; cur.unmasked = true; }
+        cur.row0 = cursor_row0(cur);
+        return false;
+      }
+      const int row0 = cursor_row0(cur);
+      const bool follows = row0 == cur.row0 + BMQ;
+      cur.row0 = row0;
+      return follows;
+    };
+    // lse2 and delta are two arrays of one workspace; (a per-lane choice between the two pointers would
+    // become a vector load of the kernel argument, and the wait for it would sit inside the loop)
+    const int64_t stat_gap = a.delta - a.lse2;
     TileDma<D, BMQ, GT> dma;
     constexpr int PASSES = TileDma<D, BMQ, GT>::PASSES;
     static_assert(PASSES <= 3, "copy instructions of a tile fit the hooks of a vector phase");
     dma.init(gtid);
-    struct CopyJob { const bf16_t* src; char* dst; uint32_t row_bytes; int rows; const float* stat_src; unsigned stat_dst; };
-    // tile t of Q (group A, with the row statistics) or dO (group B); past the end of the stream the last tile again
-    auto make_copy = [&](bool is_q, int t) {
-      const TileRef tr = locate(t < total ? t : total - 1);
+    const unsigned smem_lds = lds_addr(smem);
+    const int gwave_u = wave_u & (NW / 2 - 1);
+    struct CopyJob { const bf16_t* src; unsigned dst; uint32_t row_bytes; int rows; const float* stat_src; unsigned stat_dst; };
+    // this group's operand: Q (group A, with the row statistics) or dO (group B)
+    const bool copies_q = !group_b;
+    const bf16_t* const src_base = copies_q ? a.q + (int64_t)b * a.q_stride_b : a.d_out + (int64_t)b * a.do_stride_b;
+    const int64_t src_stride_h = copies_q ? a.q_stride_h : a.do_stride_h;
+    const int64_t src_stride_s = copies_q ? a.q_stride_s : a.do_stride_s;
+    const float* const stat_base = a.lse2 + (int64_t)b * a.n_q_heads * a.s_q + (g ? stat_gap : 0);
+    const uint32_t src_row_bytes = (uint32_t)src_stride_s * 2;
+    const int64_t src_tile_step = src_stride_s * BMQ;
+    // global addresses of the tile at the copy cursor: the tile's first row of Q / dO and of the statistics
+    struct CopySrc { const bf16_t* tile; const float* stat; };
+    auto src_at = [&](const Cursor& cc) {
+      const int h = hk * a.group + cc.hh;
+      CopySrc p;
+      p.tile = src_base + h * src_stride_h + cc.row0 * src_stride_s;
+      p.stat = stat_base + (int64_t)h * a.s_q + cc.row0;
+      return p;
+    };
+    auto src_step = [&](CopySrc& p, const Cursor& cc, bool follows) {
+      if (follows) { p.tile += src_tile_step; p.stat += BMQ; }
+      else p = src_at(cc);
+    };
+    // tile t of the stream (at the copy cursor `cc`, addresses `p`) into ring slot t % SLOTS
+    auto make_copy = [&](const Cursor& cc, const CopySrc& p, int t) {
       const int slot = t % SLOTS;
       CopyJob j;
-      if (is_q) {
-        j.src = a.q + (int64_t)b * a.q_stride_b + (int64_t)tr.h * a.q_stride_h + (int64_t)tr.row0 * a.q_stride_s;
-        j.row_bytes = (uint32_t)a.q_stride_s * 2;
-      } else {
-        j.src = a.d_out + (int64_t)b * a.do_stride_b + (int64_t)tr.h * a.do_stride_h + (int64_t)tr.row0 * a.do_stride_s;
-        j.row_bytes = (uint32_t)a.do_stride_s * 2;
-      }
-      j.dst = smem + (is_q ? L::Q_BASE : L::DO_BASE) + slot * TILE_BYTES;
-      j.rows = a.s_q - tr.row0;
+      j.src = p.tile;
+      j.row_bytes = src_row_bytes;
+      j.dst = smem_lds + (copies_q ? L::Q_BASE : L::DO_BASE) + slot * TILE_BYTES;
+      j.rows = a.s_q - cc.row0;
       // lanes 0..31: lse2 of rows row0 .. row0+31, lanes 32..63: delta of the same rows (clamped to the slice)
-      int r = tr.row0 + ql;
-      r = r < a.s_q ? r : a.s_q - 1;
-      j.stat_src = (g ? a.delta : a.lse2) + ((int64_t)b * a.n_q_heads + tr.h) * a.s_q + r;
-      j.stat_dst = __builtin_amdgcn_readfirstlane((unsigned)reinterpret_cast<uintptr_t>(
-          (__attribute__((address_space(3))) char*)(smem + L::STAT_BASE + slot * L::STAT_BYTES)));
+      const int rr = ql < j.rows ? ql : j.rows - 1;
+      j.stat_src = p.stat + rr;
+      j.stat_dst = smem_lds + L::STAT_BASE + slot * L::STAT_BYTES;
       return j;
     };
-    auto copy_pass = [&](const CopyJob& j, int n) { dma.issue(j.dst, j.src, j.row_bytes, j.rows, gtid, n); };
+    auto copy_pass = [&](const CopyJob& j, int n) { dma.issue(j.dst, j.src, j.row_bytes, j.rows, gwave_u, n); };
     // every wave of group A writes the same 64 statistics (no branch in the phase: identical data)
     auto copy_part = [&](const CopyJob& j, bool with_stats, int part) {
       if (part < PASSES) copy_pass(j, part);
@@ -629,11 +677,14 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
       const bf16_t* vbase = a.v + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h + tile_key0 * a.kv_stride_s;
       const int64_t avail = a.kv_end - tile_key0;
       for (int n = 0; n < TileDma<D, BNK, T>::PASSES; ++n)
-        dma_v.issue(smem + L::V_BASE, vbase, (uint32_t)a.kv_stride_s * 2, avail > BNK ? BNK : (int)avail, tid, n);
+        dma_v.issue(smem_lds + L::V_BASE, vbase, (uint32_t)a.kv_stride_s * 2, avail > BNK ? BNK : (int)avail, wave_u, n);
     }
-    const bool copies_q = !group_b;
-    copy_all(make_copy(copies_q, 0), copies_q);
-    copy_all(make_copy(copies_q, 1), copies_q);
+    Cursor cc = cursor_begin();          // copy cursor: two tiles ahead of the tile being worked on
+    CopySrc cp = src_at(cc);
+    copy_all(make_copy(cc, cp, 0), copies_q);
+    src_step(cp, cc, cursor_next(cc));
+    copy_all(make_copy(cc, cp, 1), copies_q);
+    src_step(cp, cc, cursor_next(cc));
     wait_async();
     TrBase<D> lo_qt;         // Q(u-1), transposed
     RpBase<D> lo_q, lo_v;    // Q(u) and this wave's V rows, row-packed
@@ -648,16 +699,17 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
       lo_qt.add(slot == 0 ? -(SLOTS - 1) * TILE_BYTES : TILE_BYTES);      // Q(u-1) sits in slot - 1
       slot = (slot == SLOTS - 1) ? 0 : slot + 1;
     };
+    Cursor mc = cursor_begin();          // the tile of the vector phase
     auto vector_phase = [&](int u, const CopyJob& j) {
       const bool need_mask = u < total_m;
       int rmin_rel = 0, rmax_rel = 32;
       if (need_mask) {
-        const TileRef tr = locate(u);
-        const int64_t rl = rmin_abs - tr.row0;
+        const int64_t rl = rmin_abs - mc.row0;
         rmin_rel = rl < 0 ? 0 : (rl > 32 ? 32 : (int)rl);
-        const int left = a.s_q - tr.row0;
+        const int left = a.s_q - mc.row0;
         rmax_rel = left > 32 ? 32 : left;
       }
+      cursor_next(mc);
       const float* stat = reinterpret_cast<const float*>(smem + L::STAT_BASE + (u % SLOTS) * L::STAT_BYTES);
       dkdv_vector_phase<D>(st, stat, c, need_mask, rmin_rel, rmax_rel, g, [&](int part) { copy_part(j, copies_q, part); });
     };
@@ -676,7 +728,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     phase_end();
     TR_MARK(tr_b2)
     for (int u = 0; u + 1 < total; ++u) {
-      vector_phase(u, make_copy(copies_q, u + 2));       // tile u+2 rides along
+      vector_phase(u, make_copy(cc, cp, u + 2));         // tile u+2 rides along
+      src_step(cp, cc, cursor_next(cc));
       TR_MARK(tr_v)
       phase_end();
       TR_MARK(tr_b1)
@@ -688,7 +741,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
       phase_end();
       TR_MARK(tr_b2)
     }
-    vector_phase(total - 1, make_copy(copies_q, total + 1));
+    vector_phase(total - 1, make_copy(cc, cp, total + 1));   // (the last tile once more)
     phase_end();
     { DkdvMatrixPhase<D, NW, true, false, 2> ph{smem, lo_qt, lo_q, lo_v, st}; ph.run(); }     // sums of the last tile
     wait_async();

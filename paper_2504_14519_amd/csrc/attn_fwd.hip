@@ -213,18 +213,20 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
     constexpr int PASSES = BN * (D / 8) / T;             // copy instructions per tile and wave
     TileDma<D, BN, T> dma;
     dma.init(tid);
+    const unsigned smem_lds = lds_addr(smem);
+    const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2;
     // quarter `part` of the copies of K(t), V(t) into set t & 1 (parts 0,1: K; 2,3: V)
     auto issue_part = [&](int t, int part) {
       if (t >= nt) return;
       const bf16_t* base = part < 2 ? kbase : vbase;
-      char* dst = smem + (part < 2 ? K_BASE : V_BASE) + (t & 1) * TILE_BYTES;
+      const unsigned dst = smem_lds + (part < 2 ? K_BASE : V_BASE) + (t & 1) * TILE_BYTES;
       const int64_t key0 = key0_of(t);
       const int64_t avail = a.kv_capacity - key0;
 #pragma unroll
       for (int n = 0; n < PASSES; ++n)
         if (PASSES == 1 ? (part & 1) == 0 : (n & 1) == (part & 1))
-          dma.issue(dst, base + key0 * a.kv_stride_s, row_bytes, avail > BN ? BN : (int)avail, tid, n);
+          dma.issue(dst, base + key0 * a.kv_stride_s, row_bytes, avail > BN ? BN : (int)avail, wave_u, n);
     };
 
     for (int part = 0; part < 4; ++part) issue_part(0, part);
@@ -344,19 +346,21 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_pp_kernel(const FwdArgs a) {
     static_assert(PASSES <= 4, "one copy instruction per softmax hook");
     dma.init(gtid);
     const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2;
-    struct CopyJob { const bf16_t* src; char* dst; int rows; };
+    const unsigned smem_lds = lds_addr(smem);
+    const int gwave_u = __builtin_amdgcn_readfirstlane(gtid >> 6);
+    struct CopyJob { const bf16_t* src; unsigned dst; int rows; };
     auto make_copy = [&](bool is_k, int t, int set) {
       const int64_t key0 = key0_of(t < nt ? t : nt - 1);
       const int64_t avail = a.kv_capacity - key0;
       CopyJob j;
       j.src = (is_k ? kbase : vbase) + key0 * a.kv_stride_s;
-      j.dst = smem + (is_k ? K_BASE : V_BASE) + set * TILE_BYTES;
+      j.dst = smem_lds + (is_k ? K_BASE : V_BASE) + set * TILE_BYTES;
       j.rows = avail > BN ? BN : (int)avail;
       return j;
     };
     auto copy_pass = [&](const CopyJob& j, int n) {
 #ifndef SLIMPIPE_NODMA
-      dma.issue(j.dst, j.src, row_bytes, j.rows, gtid, n);
+      dma.issue(j.dst, j.src, row_bytes, j.rows, gwave_u, n);
 #endif
     };
     // vector phase of tile t that also copies one tile of the next pair

@@ -229,6 +229,13 @@ struct TileStage {
 // later LDS read is assumed to alias the copy and the wave is made to wait for it on the spot.
 // Here the kernel owns the ordering: the copy targets a buffer nobody reads until the issuing wave
 // has executed wait_async() and the workgroup has passed a barrier.
+// LDS byte address of a pointer into shared memory (uniform).  Kernels take it once for the start of
+// their dynamic shared memory and do integer arithmetic from there: every cast of a generic pointer
+// costs a null check and a scalar read-back.
+SP_DEV unsigned lds_addr(const void* p) {
+  return __builtin_amdgcn_readfirstlane(
+      (unsigned)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const char*)p));
+}
 SP_DEV void dma16(const void* src, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                :: "v"(src), "s"(lds_base) : "memory", "m0");
@@ -300,12 +307,10 @@ struct TileDma {
     r0 = r;
     c16 = (uint32_t)c * 16;
   }
-  // pass n of the tile whose first row starts at `tile_base` (uniform) into LDS `tile`
-  SP_DEV void issue(char* tile, const bf16_t* tile_base, uint32_t row_bytes, int rows_avail, int tid, int n) const {
-    const int wave = tid >> 6;
-    char* dst = tile + (n * THREADS + wave * 64) * 16;            // wave-uniform
-    const unsigned lds = __builtin_amdgcn_readfirstlane(
-        (unsigned)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char*)dst));
+  // pass n of the tile whose first row starts at `tile_base` (uniform) into the LDS tile at byte address
+  // `lds_tile` (uniform); `wave` is the uniform index of the calling wave among the THREADS/64 that copy
+  SP_DEV void issue(unsigned lds_tile, const bf16_t* tile_base, uint32_t row_bytes, int rows_avail, int wave, int n) const {
+    const unsigned lds = lds_tile + (n * THREADS + wave * 64) * 16;
     int r = r0 + RPP * n;
     r = r < rows_avail ? r : rows_avail - 1;
     const uint32_t off = (uint32_t)r * row_bytes + c16;
