@@ -9,13 +9,11 @@
 //   O^T += V^T P^T     A = V through the transposed LDS read, B = P straight from the C registers
 // Scores and probabilities never leave registers.
 //
-// Schedule.  All 8 waves walk the tiles in step (S, softmax, PV, one barrier per tile).  A SIMD hosts
-// two of them, so in the S and PV parts the LDS latency of one wave is covered by the MFMAs of the
-// other.  K(t+1) and V(t+1) are copied global->LDS asynchronously into the other buffer set while
-// tile t is computed; the copy instructions are spread over the tile because the L1 path moves
-// 64 bytes per clock for the whole CU and a wave stalls at issue while it is busy.
-#include <stdlib.h>
-
+// Schedule.  A wave that has issued an MFMA issues nothing else until the matrix pipe has taken it,
+// so vector work only hides behind the MFMAs of ANOTHER wave of the same SIMD.  A wave therefore
+// alternates a matrix phase MM(t): O += P(t-1) V(t-1), S(t) = K(t) Q^T with a vector phase
+// VV(t): P(t) = softmax(S(t)); waves 0-3 (group A) and 4-7 (group B) run the same sequence shifted by
+// one phase, one workgroup barrier per phase, so every SIMD hosts one wave in each kind of phase.
 #include "kernels.hpp"
 #include "tile_common.hpp"
 
@@ -29,50 +27,14 @@ struct FwdState {
   f32x16 s[KB];
   bf16x8 p[KB][2];
   float m_run, l_run;
-  float mx;          // row maximum of the raw scores of the tile in `s` (two-group variant)
+  float mx;          // two-group kernel: maximum of this lane's raw scores over the first 32 keys of the tile in `s`
 };
 
-// S(t)^T = K(t) Q^T for this wave's 32 queries.
+// Row maxima of the raw scores of a tile, in two parts (the vector unit is the bottleneck of this
+// kernel, so the work is split evenly between the two kinds of phase): mask + maximum over the first
+// 32 keys of this half-wave's rows at the tail of the matrix phase, the rest in the vector phase.
 template <int D, int BN>
-SP_DEV void fwd_scores(const char* smem, const RpOffsets<D>& lo_k, FwdState<D, BN>& st) {
-  constexpr int KB = BN / 32, KS = D / 16;
-  __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-  for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) st.s[kb][i] = 0.f;
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb) {          // the KB accumulator chains interleaved
-      const bf16x8 ka = lds_rp<D>(smem, lo_k, ks, kb * 32 * D * 2);
-      st.s[kb] = mfma32(ka, st.qreg[ks], st.s[kb]);
-    }
-  sched_reads_ahead<KB * KS, 1, 2>();
-  __builtin_amdgcn_sched_barrier(0);
-}
-
-// O^T += V(t)^T P(t)^T.
-template <int D, int BN>
-SP_DEV void fwd_pv(const char* smem, const TrOffsets<D>& lo_v, FwdState<D, BN>& st) {
-  constexpr int KB = BN / 32, DB = D / 32;
-  __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-  for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-    for (int half = 0; half < 2; ++half)
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const bf16x8 va = lds_tr<D>(smem, lo_v, db, (kb * 32 + 16 * half) * D * 2);
-        st.o[db] = mfma32(va, st.p[kb][half], st.o[db]);
-      }
-  sched_reads_ahead<KB * 2 * DB, 2, 2>();
-  __builtin_amdgcn_sched_barrier(0);
-}
-
-// Mask the scores of a tile and take this lane's row maximum (raw scores; both half-waves combined).
-template <int D, int BN>
-SP_DEV float fwd_rowmax(FwdState<D, BN>& st, bool need_mask, int kmax_rel, int g) {
+SP_DEV float fwd_rowmax_first(FwdState<D, BN>& st, bool need_mask, int kmax_rel, int g) {
   constexpr int KB = BN / 32;
   if (need_mask) {
 #pragma unroll
@@ -85,19 +47,26 @@ SP_DEV float fwd_rowmax(FwdState<D, BN>& st, bool need_mask, int kmax_rel, int g
   }
   float mx = -INFINITY;
 #pragma unroll
-  for (int kb = 0; kb < KB; ++kb)
+  for (int i = 0; i < 16; i += 2) mx = fmaxf(fmaxf(st.s[0][i], st.s[0][i + 1]), mx);
+  return mx;
+}
+template <int D, int BN>
+SP_DEV float fwd_rowmax_rest(const FwdState<D, BN>& st, float mx) {
+  constexpr int KB = BN / 32;
 #pragma unroll
-    for (int i = 0; i < 16; i += 2) mx = fmaxf(fmaxf(st.s[kb][i], st.s[kb][i + 1]), mx);   // v_max3_f32
+  for (int kb = 1; kb < KB; ++kb)
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) mx = fmaxf(fmaxf(st.s[kb][i], st.s[kb][i + 1]), mx);
   return xhalf_max(mx);
 }
 
 // P(t) = online softmax of S(t); rescales O and the running sum when a row maximum moves.
 // kmax_rel: last visible key of this lane's query relative to the tile (>= BN: no mask needed).
-template <int D, int BN, bool PIN, bool PRE, class H>
-SP_DEV void fwd_softmax(FwdState<D, BN>& st, float c, bool need_mask, int kmax_rel, int g, H&& hook) {
+template <int D, int BN, class H>
+SP_DEV void fwd_softmax(FwdState<D, BN>& st, float c, H&& hook) {
   constexpr int KB = BN / 32, DB = D / 32;
   hook(0);
-  const float mx = PRE ? st.mx : fwd_rowmax<D, BN>(st, need_mask, kmax_rel, g);
+  const float mx = fwd_rowmax_rest<D, BN>(st, st.mx);
   hook(1);
   const float m_new = fmaxf(st.m_run, mx * c);
   const float m_eff = (m_new == -INFINITY) ? 0.f : m_new;
@@ -123,11 +92,11 @@ SP_DEV void fwd_softmax(FwdState<D, BN>& st, float c, bool need_mask, int kmax_r
     }
     st.p[kb][0] = pack8(st.s[kb], 0);
     st.p[kb][1] = pack8(st.s[kb], 8);
-    // PIN: without a use here the optimiser sinks this arithmetic past the phase barrier that follows
-    if (PIN) asm volatile("" : "+v"(st.p[kb][0]), "+v"(st.p[kb][1]));
+    // pin: without a use here the optimiser sinks this arithmetic past the phase barrier that follows
+    asm volatile("" : "+v"(st.p[kb][0]), "+v"(st.p[kb][1]));
   }
   st.l_run += l_add;
-  if (PIN) asm volatile("" : "+v"(st.l_run));
+  asm volatile("" : "+v"(st.l_run));
 }
 
 // out = O / l, lse = (m + log2 l) ln 2; rows that saw no key: out = 0, lse = -inf.
@@ -160,148 +129,80 @@ SP_DEV void fwd_epilogue(const FwdArgs& a, FwdState<D, BN>& st, int myrow, int h
   }
 }
 
+// One matrix phase of the two-group kernel as an explicit software pipeline: the 2*KB*DB MFMAs of
+// O^T += V(t-1)^T P(t-1)^T, then the KB*KS of S(t)^T = K(t) Q^T, numbered m = 0 .. N-1; the LDS reads of
+// MFMA m+LOOK are issued right before MFMA m into a ring of LOOK+1 operand buffers, and scheduling
+// fences keep that order (left to the scheduler, reads end up right in front of their MFMA whenever
+// registers are short).
+template <int D, int BN, bool WITH_PV, bool WITH_S, int LOOK>
+struct FwdMatrixPhase {
+  static constexpr int KB = BN / 32, DB = D / 32, KS = D / 16;
+  static constexpr int N_PV = WITH_PV ? 2 * KB * DB : 0, N_S = WITH_S ? KB * KS : 0, N = N_PV + N_S;
+  static constexpr int NBUF = LOOK + 1;
+  const char* smem;
+  const TrOffsets<D>& lo_v;    // V(t-1), transposed
+  const RpOffsets<D>& lo_k;    // K(t), row-packed
+  FwdState<D, BN>& st;
+  bf16x8 abuf[NBUF];
+
+  template <int M>
+  SP_DEV void reads() {
+    if constexpr (M < N_PV) {
+      constexpr int db = M % DB, blk = M / DB;                 // blk = 2*kb + half: 16 keys each
+      abuf[M % NBUF] = lds_tr<D>(smem, lo_v, db, blk * 16 * D * 2);
+    } else if constexpr (M < N) {
+      constexpr int j = M - N_PV, ks = j / KB, kb = j % KB;
+      abuf[M % NBUF] = lds_rp<D>(smem, lo_k, ks, kb * 32 * D * 2);
+    }
+  }
+  template <int M>
+  SP_DEV void mfma() {
+    if constexpr (M < N_PV) {
+      constexpr int db = M % DB, blk = M / DB;
+      st.o[db] = mfma32(abuf[M % NBUF], st.p[blk / 2][blk % 2], st.o[db]);
+    } else {
+      constexpr int j = M - N_PV, ks = j / KB, kb = j % KB;
+      const f32x16 zero = {0};
+      st.s[kb] = mfma32(abuf[M % NBUF], st.qreg[ks], ks == 0 ? zero : st.s[kb]);
+    }
+  }
+  template <int M>
+  SP_DEV void step() {
+    if constexpr (M < N) {
+      reads<M + LOOK>();
+      SP_FENCE();
+      mfma<M>();
+      SP_FENCE();
+      step<M + 1>();
+    }
+  }
+  template <int M>
+  SP_DEV void prologue() {
+    if constexpr (M < LOOK) { reads<M>(); prologue<M + 1>(); }
+  }
+  SP_DEV void run() {
+    SP_FENCE();
+    prologue<0>();
+    SP_FENCE();
+    step<0>();
+  }
+};
+
 template <int D, int NW, int BN>
 __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
-  constexpr int BM = NW * 32, KS = D / 16, DB = D / 32, T = NW * 64;
-  constexpr int TILE_BYTES = BN * D * 2;
-  static_assert((TILE_BYTES & (TILE_BYTES - 1)) == 0, "buffer toggle is an XOR");
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  // LDS: K set 0, K set 1, V set 0, V set 1
-  constexpr int K_BASE = 0, V_BASE = 2 * TILE_BYTES;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ql = lane & 31;
-  const int qblk = (int)gridDim.x - 1 - (int)blockIdx.x;   // heaviest (latest) query block first
-  const int h = blockIdx.y, b = blockIdx.z, hk = h / a.group;
-  const int m0 = qblk * BM, wrow0 = m0 + wave * 32;
-  const int myrow = wrow0 + ql;
-  const int myrow_c = myrow < a.s_q ? myrow : a.s_q - 1;
-  const int64_t qpos = a.q_offset + myrow;
-
-  FwdState<D, BN> st;
-  {
-    // Q as B operand: column = my query, k-slots = head_dim 16*ks + 8g ..
-    const bf16_t* qp = a.q + (int64_t)b * a.q_stride_b + (int64_t)myrow_c * a.q_stride_s + (int64_t)h * a.q_stride_h;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) st.qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks + 8 * g);
-  }
-#pragma unroll
-  for (int db = 0; db < DB; ++db)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) st.o[db][i] = 0.f;
-  st.m_run = -INFINITY;    // running max of score * c (log2 domain)
-  st.l_run = 0.f;          // this lane's share of the running row sum
-
-  // keys this workgroup walks: [lo, hi)
-  const int64_t lo = a.kv_begin;
-  int64_t hi = a.kv_end;
-  if (a.causal) {
-    const int last_row = (m0 + BM < a.s_q ? m0 + BM : a.s_q);   // exclusive
-    const int64_t lim = a.q_offset + last_row;
-    hi = hi < lim ? hi : lim;
-  }
-  const int nt = hi > lo ? (int)((hi - lo + BN - 1) / BN) : 0;
-  const float c = a.scale_log2e;
-
-  if (nt > 0) {
-    const bf16_t* kbase = a.k + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
-    const bf16_t* vbase = a.v + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
-    RpOffsets<D> lo_k;
-    TrOffsets<D> lo_v;
-    lo_k.init(lane, K_BASE);
-    lo_v.init(lane, V_BASE);
-    auto key0_of = [&](int t) { return lo + (int64_t)t * BN; };
-    constexpr int PASSES = BN * (D / 8) / T;             // copy instructions per tile and wave
-    TileDma<D, BN, T> dma;
-    dma.init(tid);
-    const unsigned smem_lds = lds_addr(smem);
-    const int wave_u = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2;
-    // quarter `part` of the copies of K(t), V(t) into set t & 1 (parts 0,1: K; 2,3: V)
-    auto issue_part = [&](int t, int part) {
-      if (t >= nt) return;
-      const bf16_t* base = part < 2 ? kbase : vbase;
-      const unsigned dst = smem_lds + (part < 2 ? K_BASE : V_BASE) + (t & 1) * TILE_BYTES;
-      const int64_t key0 = key0_of(t);
-      const int64_t avail = a.kv_capacity - key0;
-#pragma unroll
-      for (int n = 0; n < PASSES; ++n)
-        if (PASSES == 1 ? (part & 1) == 0 : (n & 1) == (part & 1))
-          dma.issue(dst, base + key0 * a.kv_stride_s, row_bytes, avail > BN ? BN : (int)avail, wave_u, n);
-    };
-
-    for (int part = 0; part < 4; ++part) issue_part(0, part);
-    wait_async();
-    __syncthreads();
-
-#ifdef SLIMPIPE_TRACE
-    long long tr_s = 0, tr_v = 0, tr_pv = 0, tr_b = 0, tr_w = 0, tr_t0 = clock64(), tr_w0 = wall_clock64(), tr_last = clock64();
-#define TR_MARK(var) { long long _n = clock64(); var += _n - tr_last; tr_last = _n; }
-#else
-#define TR_MARK(var)
-#endif
-    for (int t = 0; t < nt; ++t) {
-      const int64_t key0 = key0_of(t);
-      // whole tile above this wave's causal frontier -> nothing visible (the wave still helps copying)
-      const bool skip = a.causal && key0 > a.q_offset + wrow0 + 31;
-      if (!skip) {
-        issue_part(t + 1, 0);
-        issue_part(t + 1, 1);
-        fwd_scores<D, BN>(smem, lo_k, st);
-        TR_MARK(tr_s)
-        const bool need_mask = (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
-        int64_t kmax = a.kv_end - 1;
-        if (a.causal && qpos < kmax) kmax = qpos;
-        kmax -= key0;
-        const int kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
-        fwd_softmax<D, BN, false, false>(st, c, need_mask, kmax_rel, g, [](int) {});
-        TR_MARK(tr_v)
-        issue_part(t + 1, 2);
-        issue_part(t + 1, 3);
-        fwd_pv<D, BN>(smem, lo_v, st);
-        TR_MARK(tr_pv)
-      } else {
-        for (int part = 0; part < 4; ++part) issue_part(t + 1, part);
-      }
-      const int d = (t & 1) ? -TILE_BYTES : TILE_BYTES;
-      lo_k.add(d);
-      lo_v.add(d);
-      wait_async();
-      TR_MARK(tr_w)
-      __syncthreads();
-      TR_MARK(tr_b)
-    }
-#ifdef SLIMPIPE_TRACE
-    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {
-      long long* dbg = reinterpret_cast<long long*>(a.lse + (int64_t)a.n_q_heads * a.s_q);   // caller over-allocates lse
-      dbg[0] = tr_s; dbg[1] = tr_v; dbg[2] = tr_pv; dbg[3] = tr_b; dbg[4] = tr_w; dbg[5] = 0;
-      dbg[6] = clock64() - tr_t0; dbg[7] = wall_clock64() - tr_w0; dbg[8] = nt;
-    }
-#endif
-  }
-
-  fwd_epilogue<D, BN>(a, st, myrow, h, b, g);
-}
-
-// ---------------------------------------------------------------------------------------------
-// Variant with the two wave groups one phase apart.  A wave alternates a matrix phase
-// M(t): O += P(t) V(t), S(t+1) = K(t+1) Q^T  with a vector phase  V(t): P(t) = softmax(S(t)).
-// Waves 0-3 (group A) and 4-7 (group B) run the same sequence shifted by one phase, one workgroup
-// barrier per phase, so every SIMD hosts one wave in each kind of phase.  The pair (V(t), K(t+1))
-// that M(t) needs lives in one of two LDS buffer sets; the next pair is copied asynchronously during
-// the two phases before it is needed.
-template <int D, int NW, int BN>
-__global__ __launch_bounds__(NW * 64) void attn_fwd_pp_kernel(const FwdArgs a) {
   static_assert(NW == 8, "two groups of four waves");
   constexpr int BM = NW * 32, KS = D / 16, DB = D / 32, T = NW * 64;
   constexpr int TILE_BYTES = BN * D * 2;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  constexpr int K_BASE = 0, V_BASE = 2 * TILE_BYTES;
+  constexpr int KSLOTS = 3, VSLOTS = 2;
+  constexpr int K_BASE = 0, V_BASE = KSLOTS * TILE_BYTES;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ql = lane & 31;
-  const bool group_b = wave >= NW / 2;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);      // known uniform to the compiler
+  const bool group_b = wave_u >= NW / 2;
   const int qblk = (int)gridDim.x - 1 - (int)blockIdx.x;
   const int h = blockIdx.y, b = blockIdx.z, hk = h / a.group;
-  const int m0 = qblk * BM, wrow0 = m0 + wave * 32;
+  const int m0 = qblk * BM, wrow0 = m0 + wave_u * 32;
   const int myrow = wrow0 + ql;
   const int myrow_c = myrow < a.s_q ? myrow : a.s_q - 1;
   const int64_t qpos = a.q_offset + myrow;
@@ -332,13 +233,15 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_pp_kernel(const FwdArgs a) {
   if (nt > 0) {
     const bf16_t* kbase = a.k + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
     const bf16_t* vbase = a.v + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
-    RpOffsets<D> lo_k;
-    TrOffsets<D> lo_v;
     auto key0_of = [&](int t) { return lo + (int64_t)t * BN; };
-    // Tile copies are issued from vector phases only, by the four waves of the group that is in one
-    // (next to the LDS reads and MFMAs of a matrix phase they stall the wave): group B copies V(t+1)
-    // during its V(t), group A copies K(t+1) during its V(t).  Copies are branch-free: a tile past the
-    // end of the range re-copies the last tile (nobody reads it), rows past the allocation are clamped.
+    // Per tile t a wave runs the matrix phase MM(t): O^T += V(t-1)^T P(t-1)^T, S(t)^T = K(t) Q^T, row maxima
+    // of S(t); and the vector phase VV(t): P(t) = online softmax of S(t).  K(t) is read in MM(t) only, V(t) in
+    // MM(t+1) only.  Tile copies are issued from vector phases only, by the four waves of the group that
+    // is in one (next to the LDS reads and MFMAs of a matrix phase they stall the wave): group A copies
+    // K(t+2) during VV(t) into a ring of three slots, group B copies V(t+1) during its VV(t) into a ring
+    // of two, and each group waits for its copies at the end of its next matrix phase.  Copies are
+    // branch-free: a tile past the end of the range re-copies the last tile (nobody reads it), rows
+    // past the allocation are clamped.
     constexpr int GT = T / 2;                            // threads of one group
     const int gtid = tid & (GT - 1);
     TileDma<D, BN, GT> dma;
@@ -347,25 +250,24 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_pp_kernel(const FwdArgs a) {
     dma.init(gtid);
     const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2;
     const unsigned smem_lds = lds_addr(smem);
-    const int gwave_u = __builtin_amdgcn_readfirstlane(gtid >> 6);
+    const int gwave_u = wave_u & (NW / 2 - 1);
     struct CopyJob { const bf16_t* src; unsigned dst; int rows; };
-    auto make_copy = [&](bool is_k, int t, int set) {
+    auto make_copy = [&](bool is_k, int t) {
       const int64_t key0 = key0_of(t < nt ? t : nt - 1);
       const int64_t avail = a.kv_capacity - key0;
       CopyJob j;
       j.src = (is_k ? kbase : vbase) + key0 * a.kv_stride_s;
-      j.dst = smem_lds + (is_k ? K_BASE : V_BASE) + set * TILE_BYTES;
+      j.dst = smem_lds + (is_k ? K_BASE + (t % KSLOTS) * TILE_BYTES : V_BASE + (t % VSLOTS) * TILE_BYTES);
       j.rows = avail > BN ? BN : (int)avail;
       return j;
     };
-    auto copy_pass = [&](const CopyJob& j, int n) {
-#ifndef SLIMPIPE_NODMA
-      dma.issue(j.dst, j.src, row_bytes, j.rows, gwave_u, n);
-#endif
+    auto copy_pass = [&](const CopyJob& j, int n) { dma.issue(j.dst, j.src, row_bytes, j.rows, gwave_u, n); };
+    auto copy_all = [&](const CopyJob& j) {
+      for (int n = 0; n < PASSES; ++n) copy_pass(j, n);
     };
-    // vector phase of tile t that also copies one tile of the next pair
-    auto vector_phase = [&](int t, const CopyJob& j) {
-      fwd_softmax<D, BN, true, true>(st, c, false, 0, g, [&](int part) { if (part < PASSES) copy_pass(j, part); });
+    // vector phase of tile t that also copies one tile
+    auto vector_phase = [&](const CopyJob& j) {
+      fwd_softmax<D, BN>(st, c, [&](int part) { if (part < PASSES) copy_pass(j, part); });
     };
     // tail of a matrix phase: mask S(t) and take its row maxima (balances the two kinds of phase)
     auto rowmax_tile = [&](int t) {
@@ -375,117 +277,93 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_pp_kernel(const FwdArgs a) {
       if (a.causal && qpos < kmax) kmax = qpos;
       kmax -= key0;
       const int kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
-      st.mx = fwd_rowmax<D, BN>(st, need_mask, kmax_rel, g);
+      st.mx = fwd_rowmax_first<D, BN>(st, need_mask, kmax_rel, g);
       asm volatile("" : "+v"(st.mx));      // keep it on this side of the phase barrier
     };
 
-    // prologue: K(0) into K set 1 (the set "pair -1" would use), half of it by each group
-    {
-      // both groups copy the whole tile (the same bytes twice): simplest way to keep the copy code single
-      const CopyJob j = make_copy(true, 0, 1);
-      for (int n = 0; n < PASSES; ++n) copy_pass(j, n);
-    }
+    // prologue: K(0), K(1) (group A), V(0) (group B)
+    const bool copies_k = !group_b;
+    if (copies_k) { copy_all(make_copy(true, 0)); copy_all(make_copy(true, 1)); }
+    else copy_all(make_copy(false, 0));
     wait_async();
-    lo_k.init(lane, K_BASE + TILE_BYTES);   // S(t) reads K(t) from set (t-1)&1: starts at set 1
-    lo_v.init(lane, V_BASE);                // PV(t) reads V(t) from set t&1: starts at set 0
+    RpOffsets<D> lo_k;       // K(t), row-packed (registers are plentiful here: one offset per head_dim block)
+    TrOffsets<D> lo_v;       // V(t-1), transposed
+    lo_k.init(lane, K_BASE);
+    lo_v.init(lane, V_BASE + TILE_BYTES);        // "V(-1)": never read
     __syncthreads();
 
-    if (!group_b) {
-      // phase 0
-      fwd_scores<D, BN>(smem, lo_k, st);
-      rowmax_tile(0);
-      lo_k.add(-TILE_BYTES);
-      phase_end();
+    int kslot = 0, vslot = 1;       // slots of K(t) and V(t-1)
+    auto advance = [&]() {
+      lo_k.add(kslot == KSLOTS - 1 ? -(KSLOTS - 1) * TILE_BYTES : TILE_BYTES);
+      lo_v.add(vslot ? -TILE_BYTES : TILE_BYTES);
+      kslot = (kslot == KSLOTS - 1) ? 0 : kslot + 1;
+      vslot ^= 1;
+    };
 #ifdef SLIMPIPE_TRACE
-      long long tp_v = 0, tp_w = 0, tp_b1 = 0, tp_pv = 0, tp_s = 0, tp_b2 = 0, tp_t0 = clock64(), tp_w0 = wall_clock64(), tp_last = clock64();
+    long long tp_v = 0, tp_w = 0, tp_b1 = 0, tp_m = 0, tp_b2 = 0, tp_t0 = clock64(), tp_w0 = wall_clock64(), tp_last = clock64();
 #define TP_MARK(var) { long long _n = clock64(); var += _n - tp_last; tp_last = _n; }
 #else
 #define TP_MARK(var)
 #endif
-      for (int t = 0; t < nt; ++t) {
-        // phase 2t+1: vector phase, copying K(t+1) for the matrix phase that follows
-        vector_phase(t, make_copy(true, t + 1, t & 1));
-        TP_MARK(tp_v)
-        wait_async();
-        TP_MARK(tp_w)
-        phase_end();
-        TP_MARK(tp_b1)
-        // phase 2t+2: matrix phase
-        fwd_pv<D, BN>(smem, lo_v, st);
-        TP_MARK(tp_pv)
-        if (t + 1 < nt) {
-          fwd_scores<D, BN>(smem, lo_k, st);
-          rowmax_tile(t + 1);
-        }
-        const int d = (t & 1) ? -TILE_BYTES : TILE_BYTES;
-        lo_k.add(d);
-        lo_v.add(d);
-        TP_MARK(tp_s)
-        phase_end();
-        TP_MARK(tp_b2)
-      }
-#ifdef SLIMPIPE_TRACE
-      if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {
-        long long* dbg = reinterpret_cast<long long*>(a.lse + (int64_t)a.n_q_heads * a.s_q);   // caller over-allocates lse
-        dbg[0] = tp_v; dbg[1] = tp_w; dbg[2] = tp_b1; dbg[3] = tp_pv; dbg[4] = tp_s; dbg[5] = tp_b2;
-        dbg[6] = clock64() - tp_t0; dbg[7] = wall_clock64() - tp_w0; dbg[8] = nt;
-      }
-#endif
-      phase_end();                          // group B's last matrix phase
-    } else {
-      // phase 0: nothing to compute yet; V(0)
-      {
-        const CopyJob j = make_copy(false, 0, 0);
-        for (int n = 0; n < PASSES; ++n) copy_pass(j, n);
-      }
+    // Both groups run the same code; group B starts one phase (one barrier) later and group A idles
+    // one phase at the end.
+    if (group_b) phase_end();
+    { FwdMatrixPhase<D, BN, false, true, 2> ph{smem, lo_v, lo_k, st}; ph.run(); }
+    rowmax_tile(0);
+    advance();
+    wait_async();
+    phase_end();
+    TP_MARK(tp_b2)
+    for (int t = 0; t + 1 < nt; ++t) {
+      vector_phase(copies_k ? make_copy(true, t + 2) : make_copy(false, t + 1));
+      TP_MARK(tp_v)
       phase_end();
-      // phase 1
-      fwd_scores<D, BN>(smem, lo_k, st);
-      rowmax_tile(0);
-      lo_k.add(-TILE_BYTES);
-      wait_async();
+      TP_MARK(tp_b1)
+      { FwdMatrixPhase<D, BN, true, true, 2> ph{smem, lo_v, lo_k, st}; ph.run(); }
+      rowmax_tile(t + 1);
+      advance();
+      TP_MARK(tp_m)
+      wait_async();                                      // the copies of the vector phase before have landed
+      TP_MARK(tp_w)
       phase_end();
-      for (int t = 0; t < nt; ++t) {
-        // phase 2t+2: vector phase, copying V(t+1)
-        vector_phase(t, make_copy(false, t + 1, (t + 1) & 1));
-        phase_end();
-        // phase 2t+3: matrix phase
-        fwd_pv<D, BN>(smem, lo_v, st);
-        if (t + 1 < nt) {
-          fwd_scores<D, BN>(smem, lo_k, st);
-          rowmax_tile(t + 1);
-        }
-        const int d = (t & 1) ? -TILE_BYTES : TILE_BYTES;
-        lo_k.add(d);
-        lo_v.add(d);
-        wait_async();
-        phase_end();
-      }
+      TP_MARK(tp_b2)
     }
+    vector_phase(copies_k ? make_copy(true, nt + 1) : make_copy(false, nt));
+    phase_end();
+    { FwdMatrixPhase<D, BN, true, false, 2> ph{smem, lo_v, lo_k, st}; ph.run(); }
+    wait_async();
+    phase_end();
+    if (!group_b) phase_end();
+#ifdef SLIMPIPE_TRACE
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {
+      long long* dbg = reinterpret_cast<long long*>(a.lse + (int64_t)a.n_q_heads * a.s_q);   // caller over-allocates lse
+      dbg[0] = tp_v; dbg[1] = tp_w; dbg[2] = tp_b1; dbg[3] = tp_m; dbg[4] = 0; dbg[5] = tp_b2;
+      dbg[6] = clock64() - tp_t0; dbg[7] = wall_clock64() - tp_w0; dbg[8] = nt;
+    }
+#endif
   }
   fwd_epilogue<D, BN>(a, st, myrow, h, b, g);
 }
 
-template <int D, int NW, int BN, bool PP>
+template <int D, int NW, int BN>
 static hipError_t launch_fwd_t(const FwdArgs& a, int batch, hipStream_t st) {
   constexpr int BM = NW * 32;
-  const size_t smem = (size_t)4 * BN * D * 2;
-  auto kern = PP ? &attn_fwd_pp_kernel<D, NW, BN> : &attn_fwd_kernel<D, NW, BN>;
+  const size_t smem = (size_t)5 * BN * D * 2;       // K ring of three, V ring of two
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_kernel<D, NW, BN>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   dim3 grid((a.s_q + BM - 1) / BM, a.n_q_heads, batch), block(NW * 64);
-  hipLaunchKernelGGL(kern, grid, block, smem, st, a);
+  hipLaunchKernelGGL((attn_fwd_kernel<D, NW, BN>), grid, block, smem, st, a);
   return hipGetLastError();
 }
 
 hipError_t launch_fwd(const FwdArgs& a, int batch, int head_dim, hipStream_t st) {
-  static const int pp = [] { const char* e = getenv("SLIMPIPE_FWD_PP"); return e ? atoi(e) : 1; }();
-  if (head_dim == 128) return pp ? launch_fwd_t<128, 8, 64, true>(a, batch, st) : launch_fwd_t<128, 8, 64, false>(a, batch, st);
-  return pp ? launch_fwd_t<64, 8, 64, true>(a, batch, st) : launch_fwd_t<64, 8, 64, false>(a, batch, st);
+  if (head_dim == 128) return launch_fwd_t<128, 8, 64>(a, batch, st);
+  return launch_fwd_t<64, 8, 64>(a, batch, st);
 }
 
 }  // namespace slimpipe

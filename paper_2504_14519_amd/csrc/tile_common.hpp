@@ -72,32 +72,15 @@ SP_DEV int tile_off(int row, int chunk) {
   }
 }
 
-// Row-packed operand: 8 consecutive head_dim elements [16*ks + 8g, +8) of tile row `row`.
-template <int D>
-SP_DEV bf16x8 lds_read_rowpacked(const char* tile, int row, int ks, int g) {
-  return *reinterpret_cast<const bf16x8*>(tile + tile_off<D>(row, 2 * ks + g));
-}
-
-// Transposed operand through ds_read_b64_tr_b16.  Within each block of 16 lanes the instruction
-// returns to lane i, element e, the (i%4)-th 16-bit element of the 8 bytes addressed by lane
-// 4e + i/4 of the block.  Pointing lane j of block b at row (row0 + 4*(b>>1) + j/4), columns
-// 32*db + 16*(b&1) + 4*(j%4) .. +3 therefore hands lane l the column 32*db + (l&31) of rows
-// row0 + 4g .. row0 + 4g+3; a second read 8 rows further completes the 8 k-slots of group g.
-template <int D>
-SP_DEV bf16x8 lds_read_transposed(const char* tile, int row0, int db, int lane) {
-  const int j = lane & 15, b = lane >> 4;
-  const int row = row0 + ((b >> 1) << 2) + (j >> 2);
-  const int chunk = 4 * db + 2 * (b & 1) + ((j & 3) >> 1);
-  const int sub = (j & 1) << 3;
-  typedef bf16x4 __attribute__((address_space(3))) * lds_v4_ptr;
-  bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4_ptr)(tile + tile_off<D>(row, chunk) + sub));
-  bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4_ptr)(tile + tile_off<D>(row + 8, chunk) + sub));
-  bf16x8 r;
-  r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
-  r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
-  return r;
-}
-
+// The two LDS read patterns.
+//   Row-packed operand (contraction over head_dim): lane (r, g) reads the 8 consecutive head_dim
+//   elements [16*ks + 8g, +8) of tile row r with one ds_read_b128.
+//   Transposed operand (contraction over rows) through ds_read_b64_tr_b16: within each block of 16
+//   lanes the instruction returns to lane i, element e, the (i%4)-th 16-bit element of the 8 bytes
+//   addressed by lane 4e + i/4 of the block.  Pointing lane j of block b at row (row0 + 4*(b>>1) + j/4),
+//   columns 32*db + 16*(b&1) + 4*(j%4) .. +3 therefore hands lane l the column 32*db + (l&31) of rows
+//   row0 + 4g .. row0 + 4g+3; a second read 8 rows further completes the 8 k-slots of group g.
+//
 // Per-lane byte offsets of the two read patterns for a tile row block that starts at a multiple of
 // 16 rows.  Adding a multiple of 16 rows does not change the swizzle bits, so every read of a
 // kernel is (one of these registers) + (compile-time constant): the constant goes into the
@@ -188,39 +171,6 @@ SP_DEV bf16x8 lds_tr(const char* smem, const TrBase<D>& lo, int db, int const_of
   return r;
 }
 
-// Cooperative staging of a ROWS x D bf16 tile: global -> registers (issue early) -> LDS (commit late).
-// Row r of the tile is global row min(row0 + r, row_last); callers mask what the clamp duplicates.
-template <int D, int ROWS, int THREADS>
-struct TileStage {
-  static constexpr int NC = D / 8;
-  static constexpr int CHUNKS = ROWS * NC;
-  static constexpr int PER_THREAD = (CHUNKS + THREADS - 1) / THREADS;
-  u32x4 regs[PER_THREAD];
-
-  SP_DEV void issue(const bf16_t* base, int64_t row_stride, int64_t row0, int64_t row_last, int tid) {
-#pragma unroll
-    for (int n = 0; n < PER_THREAD; ++n) {
-      const int id = tid + n * THREADS;
-      if (CHUNKS % THREADS == 0 || id < CHUNKS) {
-        const int r = id / NC, c = id % NC;
-        int64_t gr = row0 + r;
-        gr = gr < row_last ? gr : row_last;
-        regs[n] = *reinterpret_cast<const u32x4*>(base + gr * row_stride + c * 8);
-      }
-    }
-  }
-  SP_DEV void commit(char* tile, int tid) const {
-#pragma unroll
-    for (int n = 0; n < PER_THREAD; ++n) {
-      const int id = tid + n * THREADS;
-      if (CHUNKS % THREADS == 0 || id < CHUNKS) {
-        const int r = id / NC, c = id % NC;
-        *reinterpret_cast<u32x4*>(tile + tile_off<D>(r, c)) = regs[n];
-      }
-    }
-  }
-};
-
 // Asynchronous staging of a ROWS x D bf16 tile with global_load_lds_dwordx4: every lane hands in a
 // global address, the hardware writes the 16 bytes of lane L of a wave to (M0 = wave-uniform LDS
 // base) + 16*L.  One wave instruction therefore fills 1 KB of consecutive PHYSICAL chunks; the lane
@@ -228,7 +178,9 @@ struct TileStage {
 // The instruction is issued from inline assembly on purpose: through the compiler builtin every
 // later LDS read is assumed to alias the copy and the wave is made to wait for it on the spot.
 // Here the kernel owns the ordering: the copy targets a buffer nobody reads until the issuing wave
-// has executed wait_async() and the workgroup has passed a barrier.
+// has executed wait_async() and the workgroup has passed a barrier.  The assembly statements are
+// compiler barriers for memory operations: an LDS read written after one is not moved above it.
+
 // LDS byte address of a pointer into shared memory (uniform).  Kernels take it once for the start of
 // their dynamic shared memory and do integer arithmetic from there: every cast of a generic pointer
 // costs a null check and a scalar read-back.
@@ -236,60 +188,13 @@ SP_DEV unsigned lds_addr(const void* p) {
   return __builtin_amdgcn_readfirstlane(
       (unsigned)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const char*)p));
 }
-SP_DEV void dma16(const void* src, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :: "v"(src), "s"(lds_base) : "memory", "m0");
-}
 // one dword per lane: lane i lands at lds_base + 4*i
 SP_DEV void dma4(const void* src, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
                :: "v"(src), "s"(lds_base) : "memory", "m0");
 }
-template <int D, int ROWS, int THREADS>
-SP_DEV void tile_load_async(char* tile, const bf16_t* base, int64_t row_stride, int64_t row0, int64_t row_last, int tid) {
-  constexpr int NC = D / 8;
-  constexpr int CHUNKS = ROWS * NC;
-  static_assert(CHUNKS % THREADS == 0, "tile must be a whole number of passes");
-  const int wave = tid >> 6;
-#pragma unroll
-  for (int n = 0; n < CHUNKS / THREADS; ++n) {
-    const int id = tid + n * THREADS;
-    const int r = id / NC, p = id % NC;
-    int c;
-    if constexpr (D == 128) c = ((((p >> 2) ^ r) & 3) << 2) | (((p & 3) ^ (r >> 2)) & 3);
-    else c = (p ^ r) & (NC - 1);
-    int64_t gr = row0 + r;
-    gr = gr < row_last ? gr : row_last;
-    const bf16_t* src = base + gr * row_stride + c * 8;
-    char* dst = tile + (n * THREADS + wave * 64) * 16;            // wave-uniform
-    const unsigned lds = __builtin_amdgcn_readfirstlane(
-        (unsigned)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char*)dst));
-    dma16(src, lds);
-  }
-}
-// One pass (THREADS chunks = THREADS/NC rows) of the same staging, so that a kernel can spread the
-// passes of a tile over a phase: the L1 path moves 64 bytes per clock for the whole CU and a wave
-// stalls at issue while it is busy.
-template <int D, int THREADS>
-SP_DEV void tile_load_async_pass(char* tile, const bf16_t* base, int64_t row_stride, int64_t row0, int64_t row_last,
-                                 int tid, int n) {
-  constexpr int NC = D / 8;
-  const int wave = tid >> 6;
-  const int id = tid + n * THREADS;
-  const int r = id / NC, p = id % NC;
-  int c;
-  if constexpr (D == 128) c = ((((p >> 2) ^ r) & 3) << 2) | (((p & 3) ^ (r >> 2)) & 3);
-  else c = (p ^ r) & (NC - 1);
-  int64_t gr = row0 + r;
-  gr = gr < row_last ? gr : row_last;
-  const bf16_t* src = base + gr * row_stride + c * 8;
-  char* dst = tile + (n * THREADS + wave * 64) * 16;            // wave-uniform
-  const unsigned lds = __builtin_amdgcn_readfirstlane(
-      (unsigned)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) char*)dst));
-  dma16(src, lds);
-}
-// The same staging with nothing but two per-lane constants: THREADS/NC rows per pass with
-// THREADS a multiple of 16*NC... (THREADS = 256, NC = 16: 16 rows per pass), so pass n handles row
+// A tile copy with nothing but two per-lane constants: THREADS/NC rows per pass with THREADS a
+// multiple of 16*NC (THREADS = 256, NC = 16: 16 rows per pass), so pass n handles row
 // r0 + (THREADS/NC)*n of the tile and, the row step being a multiple of 16, the SAME swizzled chunk.
 // A tile copy is "uniform base + 32-bit lane offset" with the row clamped to the rows that exist
 // (`rows_avail` >= 1, uniform): branch-free, four VALU operations per copy instruction.
@@ -324,26 +229,6 @@ SP_DEV void wait_async() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 // ---- scheduling helpers ------------------------------------------------------------------------
 #define SP_FENCE() __builtin_amdgcn_sched_barrier(0)
-// instruction classes of __builtin_amdgcn_sched_group_barrier
-#define SP_SG_VALU 0x2
-#define SP_SG_MFMA 0x8
-#define SP_SG_DSRD 0x100
-
-// Ask the scheduler for "LDS reads LOOK MFMAs ahead of their use": a block of reads first, then one
-// MFMA followed by the reads of the MFMA LOOK places later.  An LDS read takes several MFMA times to
-// come back and a wave issues in order, so reads placed right before their MFMA stall it.
-// (LOOK = 2 measured best; deeper look-ahead made the schedules worse.)
-template <int N_MFMA, int READS_PER_MFMA, int LOOK>
-SP_DEV void sched_reads_ahead() {
-  __builtin_amdgcn_sched_group_barrier(SP_SG_DSRD, LOOK * READS_PER_MFMA, 0);
-#pragma unroll
-  for (int i = 0; i < N_MFMA - LOOK; ++i) {
-    __builtin_amdgcn_sched_group_barrier(SP_SG_MFMA, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(SP_SG_DSRD, READS_PER_MFMA, 0);
-  }
-  __builtin_amdgcn_sched_group_barrier(SP_SG_MFMA, LOOK, 0);
-}
-
 // End of a phase of the two-group schedules: nothing may be scheduled across the barrier.
 SP_DEV void phase_end() {
   __builtin_amdgcn_sched_barrier(0);
