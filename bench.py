@@ -86,7 +86,9 @@ def main():
     dv_acc = torch.zeros((1, N, Hkv, D), device=dev, dtype=torch.float32)
     dk_out = torch.empty((1, N, Hkv, D), device=dev, dtype=torch.bfloat16)
     dv_out = torch.empty((1, N, Hkv, D), device=dev, dtype=torch.bfloat16)
-    ws_bytes = sp.slimpipe_attn_workspace_bytes(sp.make_params(q[:, :s], k, outs[0], 0, 0, s, True, scale), True)
+    # one workspace for every backward call of the step: the largest any slice asks for
+    ws_bytes = max(sp.slimpipe_attn_workspace_bytes(sp.make_params(q[:, :s], k, outs[0], i * s, 0, (i + 1) * s, True, scale), True)
+                   for i in slices)
     ws = torch.empty(ws_bytes, device=dev, dtype=torch.uint8)
 
     def qs(j):

@@ -75,9 +75,14 @@ typedef struct slimpipe_attn_params {
  * backward needs).  No device access. */
 int slimpipe_attn_validate(const slimpipe_attn_params* p, int is_bwd);
 
-/* Bytes of device workspace the call needs (0 for forward; for backward two floats per
- * (batch, q head, row): delta = rowsum(d_out * out) and lse in log2 units, each array rounded up
- * to 256 bytes). */
+/* Bytes of device workspace the call would like (0 for forward).  Backward needs two floats per
+ * (batch, q head, row): delta = rowsum(d_out * out) and lse in log2 units, each array rounded up to
+ * 256 bytes; slimpipe_attn_bwd refuses less.  On top of that it can use room for partial dk/dv sums:
+ * when the key tiles of a call do not fill the GPU's compute units evenly, the query rows of each
+ * key tile are cut into 2, 4 or 8 chunks that run as workgroups of their own, each writing float32
+ * partial sums [chunk][dk, dv][batch][kv head][keys rounded up to 256][head_dim] that a second kernel adds up
+ * in chunk order.  The figure returned here includes that room for the split this call would pick;
+ * given less, slimpipe_attn_bwd uses the largest split that fits (down to none). */
 int slimpipe_attn_workspace_bytes(const slimpipe_attn_params* p, int is_bwd, size_t* bytes);
 
 /* Forward of one query slice against keys [kv_begin, kv_end) of the cached prefix
@@ -95,9 +100,10 @@ int slimpipe_attn_fwd(const slimpipe_attn_params* p,
  *              Uses the q strides.
  *   dk_acc, dv_acc : float32 with the kv strides; rows [kv_begin, kv_end) are overwritten
  *              (dkv_accumulate == 0) or incremented (!= 0); other rows are untouched.  Each row is
- *              owned by one workgroup that sums queries and the heads of a GQA group in a fixed
- *              order, so results are bit-reproducible from run to run.
- * Enqueues: delta pre-pass, dq kernel, dk/dv kernel. */
+ *              owned by one workgroup (or a fixed number of them whose partial sums are added in a
+ *              fixed order) that sums queries and the heads of a GQA group in a fixed order, so
+ *              results are bit-reproducible from run to run for the same workspace size.
+ * Enqueues: delta pre-pass, dq kernel, dk/dv kernel, and the reduce kernel when the stream is split. */
 int slimpipe_attn_bwd(const slimpipe_attn_params* p,
                       const void* q_slice, const void* k_prefix, const void* v_prefix,
                       const void* out, const void* d_out, const float* lse,
@@ -127,7 +133,7 @@ const char* slimpipe_attn_strerror(int code);
  * since the last read and clears the records.  The only state the library keeps; not thread-safe. */
 enum {
   SLIMPIPE_KERNEL_FWD = 0, SLIMPIPE_KERNEL_DELTA = 1, SLIMPIPE_KERNEL_DQ = 2, SLIMPIPE_KERNEL_DKDV = 3,
-  SLIMPIPE_KERNEL_MERGE = 4, SLIMPIPE_KERNEL_FINALIZE = 5, SLIMPIPE_KERNEL_KINDS = 6
+  SLIMPIPE_KERNEL_MERGE = 4, SLIMPIPE_KERNEL_FINALIZE = 5, SLIMPIPE_KERNEL_DKDV_REDUCE = 6, SLIMPIPE_KERNEL_KINDS = 7
 };
 int slimpipe_attn_profile_enable(int enable);
 int slimpipe_attn_profile_read(double total_ms[SLIMPIPE_KERNEL_KINDS], int64_t launches[SLIMPIPE_KERNEL_KINDS]);

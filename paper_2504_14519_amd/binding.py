@@ -176,7 +176,7 @@ def slimpipe_attn_finalize_bf16(acc, dst=None):
     return dst
 
 
-KERNEL_KINDS = ("fwd", "delta", "dq", "dkdv", "merge", "finalize")
+KERNEL_KINDS = ("fwd", "delta", "dq", "dkdv", "merge", "finalize", "dkdv_reduce")
 
 
 def slimpipe_attn_profile_enable(enable):

@@ -1,5 +1,6 @@
 // C ABI of the library: host-only validation, launch planning, error mapping.
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <vector>
@@ -20,6 +21,48 @@ size_t stat_bytes(const slimpipe_attn_params* p) {
   return (n + 255) & ~(size_t)255;
 }
 size_t delta_bytes(const slimpipe_attn_params* p) { return 2 * stat_bytes(p); }
+
+// Compute units of the current device (256 on MI355X, also assumed when no device can be asked).
+int compute_units() {
+  static const int n = [] {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+    return cus;
+  }();
+  return n;
+}
+
+// The dk/dv kernel runs one workgroup per compute unit; a call with W key tiles takes ceil(W / CUs)
+// rounds of one tile's query stream each.  Cutting every stream into S chunks makes W*S workgroups of
+// 1/S the length: S is the smallest of 1, 2, 4, 8 that comes within 3% of the best rounds/S, as long
+// as a chunk keeps at least 64 query tiles (the prologue and epilogue of a workgroup cost a few tiles).
+int64_t dkdv_key_tiles(const slimpipe_attn_params* p) {
+  const int64_t nkeys = p->kv_end - p->kv_begin, per = dkdv_keys_per_workgroup();
+  return nkeys > 0 ? (nkeys + per - 1) / per : 0;
+}
+int preferred_split(const slimpipe_attn_params* p) {
+  const int64_t tiles = dkdv_key_tiles(p);
+  const int64_t w = tiles * p->n_kv_heads * p->batch;
+  if (w <= 0) return 1;
+  const int64_t stream = ((int64_t)p->s_q + 31) / 32 * (p->n_q_heads / p->n_kv_heads);
+  const int cus = compute_units();
+  double best = 1e30;
+  double cost[4];
+  for (int i = 0; i < 4; ++i) {
+    const int s = 1 << i;
+    cost[i] = (s > 1 && stream / s < 64) ? 1e30 : (double)((w * s + cus - 1) / cus) / s;
+    if (cost[i] < best) best = cost[i];
+  }
+  for (int i = 0; i < 4; ++i)
+    if (cost[i] <= best * 1.03) return 1 << i;
+  return 1;
+}
+size_t split_bytes(const slimpipe_attn_params* p, int split) {
+  if (split <= 1) return 0;
+  return (size_t)split * 2 * (size_t)p->batch * (size_t)p->n_kv_heads * (size_t)(dkdv_key_tiles(p) * dkdv_keys_per_workgroup()) *
+         (size_t)p->head_dim * sizeof(float);
+}
 
 
 // ---- optional per-kernel event timing -------------------------------------------------------
@@ -104,7 +147,7 @@ int slimpipe_attn_workspace_bytes(const slimpipe_attn_params* p, int is_bwd, siz
   if (!bytes) return SLIMPIPE_EINVAL_NULL;
   int rc = slimpipe_attn_validate(p, is_bwd);
   if (rc != SLIMPIPE_OK) return rc;
-  *bytes = is_bwd ? delta_bytes(p) : 0;
+  *bytes = is_bwd ? delta_bytes(p) + split_bytes(p, preferred_split(p)) : 0;
   return SLIMPIPE_OK;
 }
 
@@ -163,6 +206,12 @@ int slimpipe_attn_bwd(const slimpipe_attn_params* p, const void* q_slice, const 
   a.delta = static_cast<float*>(workspace);
   a.lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + stat_bytes(p));
   a.dq = dq; a.dk_acc = dk_acc; a.dv_acc = dv_acc;
+  int split = preferred_split(p);
+  if (const char* e = getenv("SLIMPIPE_EXP_SPLIT")) split = atoi(e);
+  while (split > 1 && delta_bytes(p) + split_bytes(p, split) > workspace_bytes) split /= 2;
+  a.n_split = split;
+  a.part = reinterpret_cast<float*>(static_cast<char*>(workspace) + delta_bytes(p));
+  a.nkeys_pad = dkdv_key_tiles(p) * dkdv_keys_per_workgroup();
   a.s_q = p->s_q; a.n_q_heads = p->n_q_heads; a.n_kv_heads = p->n_kv_heads;
   a.group = p->n_q_heads / p->n_kv_heads; a.causal = p->causal;
   a.dq_f32 = (dq_dtype == SLIMPIPE_F32); a.dq_accumulate = dq_accumulate ? 1 : 0;
@@ -177,6 +226,9 @@ int slimpipe_attn_bwd(const slimpipe_attn_params* p, const void* q_slice, const 
   if (timed(SLIMPIPE_KERNEL_DELTA, st, [&] { return launch_delta(a, p->batch, p->head_dim, st); }) != hipSuccess) return SLIMPIPE_ELAUNCH;
   if (timed(SLIMPIPE_KERNEL_DQ, st, [&] { return launch_bwd_dq(a, p->batch, p->head_dim, st); }) != hipSuccess) return SLIMPIPE_ELAUNCH;
   if (timed(SLIMPIPE_KERNEL_DKDV, st, [&] { return launch_bwd_dkdv(a, p->batch, p->head_dim, st); }) != hipSuccess) return SLIMPIPE_ELAUNCH;
+  if (split > 1 &&
+      timed(SLIMPIPE_KERNEL_DKDV_REDUCE, st, [&] { return launch_dkdv_reduce(a, p->batch, p->head_dim, st); }) != hipSuccess)
+    return SLIMPIPE_ELAUNCH;
   return SLIMPIPE_OK;
 }
 

@@ -167,12 +167,14 @@ template <int D, int BN, class H>
 SP_DEV void dq_vector_phase(DqState<D, BN>& st, float c, bool need_mask, int kmax_rel, int g, H&& hook) {
   constexpr int KB = BN / 32;
   if (need_mask) {
+    const int kmax_lane = kmax_rel - 4 * g;
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        const int key_rel = kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-        st.s[kb][i] = key_rel <= kmax_rel ? st.s[kb][i] : -INFINITY;     // exp2(-inf) = 0
+        // key (kb*32 + 8*(i/4) + 4g + i%4) <= kmax_rel, with the lane's part on the right: the left side is
+        // an immediate (a register per element otherwise, hoisted out of the tile loop)
+        st.s[kb][i] = (kb * 32 + 8 * (i >> 2) + (i & 3)) <= kmax_lane ? st.s[kb][i] : -INFINITY;     // exp2(-inf) = 0
       }
   }
 #pragma unroll
@@ -490,30 +492,34 @@ template <int D, class H>
 SP_DEV void dkdv_vector_phase(DkdvState<D>& st, const float* stat, float c, bool need_mask, int rmin_rel, int rmax_rel,
                               int g, H&& hook) {
   if (need_mask) {
+    // row (8*(i/4) + 4g + i%4) in [rmin_rel, rmax_rel), with the lane's part moved to the bounds: the row
+    // numbers are immediates then (a register per element otherwise, hoisted out of the tile loop)
+    const int lo = rmin_rel - 4 * g, hi = rmax_rel - 4 * g;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      const int r = 8 * (i >> 2) + 4 * g + (i & 3);
-      st.s[i] = ((r >= rmin_rel) & (r < rmax_rel)) ? st.s[i] : -INFINITY;      // exp2(-inf) = 0
+      const int r = 8 * (i >> 2) + (i & 3);
+      st.s[i] = ((r >= lo) & (r < hi)) ? st.s[i] : -INFINITY;      // exp2(-inf) = 0
     }
   }
-  // all row statistics first: the copy instructions in the hooks are compiler barriers for memory
-  // operations, and an LDS read placed after one would be waited for on the spot
-  f32x4 l4[4], d4[4];
+  // Stage by stage over all 16 elements, so that neighbouring instructions do not depend on each other.
+  // The row statistics are read in two batches that share registers (this phase is the register peak
+  // of the kernel): lse2 up front, delta once lse2 is used up, its latency behind the exponentials.  The
+  // copy instructions in the hooks are compiler barriers for memory operations: an LDS read written
+  // after one is not moved above it.
+  f32x4 st4[4];
 #pragma unroll
-  for (int i4 = 0; i4 < 4; ++i4) {
-    l4[i4] = *reinterpret_cast<const f32x4*>(stat + 8 * i4 + 4 * g);
-    d4[i4] = *reinterpret_cast<const f32x4*>(stat + 32 + 8 * i4 + 4 * g);
-  }
-  // stage by stage over all 16 elements, so that neighbouring instructions do not depend on each other
+  for (int i4 = 0; i4 < 4; ++i4) st4[i4] = *reinterpret_cast<const f32x4*>(stat + 8 * i4 + 4 * g);
   hook(0);
 #pragma unroll
-  for (int i = 0; i < 16; ++i) st.s[i] = __builtin_fmaf(st.s[i], c, -l4[i >> 2][i & 3]);
+  for (int i = 0; i < 16; ++i) st.s[i] = __builtin_fmaf(st.s[i], c, -st4[i >> 2][i & 3]);
+  asm volatile("" : "+v"(st.s));          // lse2 is dead from here on
   hook(1);
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    st.s[i] = exp2_fast(st.s[i]);
-    st.dp[i] -= d4[i >> 2][i & 3];
-  }
+  for (int i4 = 0; i4 < 4; ++i4) st4[i4] = *reinterpret_cast<const f32x4*>(stat + 32 + 8 * i4 + 4 * g);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) st.s[i] = exp2_fast(st.s[i]);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) st.dp[i] -= st4[i >> 2][i & 3];
   hook(2);
 #pragma unroll
   for (int i = 0; i < 16; ++i) st.dp[i] *= st.s[i];
@@ -540,7 +546,11 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
   const bool group_b = wave_u >= NW / 2;
   const int gtid = tid & (GT - 1);
   const int hk = blockIdx.y, b = blockIdx.z;
-  const int64_t tile_key0 = a.kv_begin + (int64_t)blockIdx.x * BNK;
+  // blockIdx.x = key tile * n_split + chunk of that tile's query stream
+  // (the quotients come out of vector instructions: read them back so that the compiler knows they are uniform)
+  const int ktile = __builtin_amdgcn_readfirstlane((int)(blockIdx.x / (unsigned)a.n_split));
+  const int split = (int)blockIdx.x - ktile * a.n_split;
+  const int64_t tile_key0 = a.kv_begin + (int64_t)ktile * BNK;
   const int64_t mykey = tile_key0 + wave_u * 32 + ql;
   const int64_t mykey_c = mykey < a.kv_end ? mykey : a.kv_end - 1;
 
@@ -576,9 +586,12 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
   const int total_m = nm * a.group, total = (nm + nu) * a.group;
   const float c = a.scale_log2e;
   // first row (within the slice) that sees this lane's key
-  const int64_t rmin_abs = a.causal ? mykey - a.q_offset : 0;
+  // this workgroup's part of the stream: tiles [seq_lo, seq_hi)
+  const int seq_lo = __builtin_amdgcn_readfirstlane((int)((int64_t)total * split / a.n_split));
+  const int seq_hi = __builtin_amdgcn_readfirstlane((int)((int64_t)total * (split + 1) / a.n_split));
+  const int cnt = seq_hi - seq_lo;
 
-  if (total > 0) {
+  if (cnt > 0) {
     // Position in the stream of query tiles: masked tiles of head 0, 1, .. of the group, then the unmasked
     // tiles of head 0, 1, ..  Stepping it is a few scalar additions when the next tile follows in the
     // same head (no division, no 64-bit product: a wave issues in order and a chain of scalar
@@ -593,14 +606,17 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     };
     auto cursor_begin = [&]() {
       Cursor cur;
-      cur.seq = 0; cur.hh = 0; cur.r = 0;
-      cur.unmasked = nm == 0;
+      cur.seq = seq_lo;
+      cur.unmasked = seq_lo >= total_m;
+      const int u = cur.unmasked ? seq_lo - total_m : seq_lo, per = cur.unmasked ? nu : nm;   // per > 0: the chunk is not empty
+      cur.hh = __builtin_amdgcn_readfirstlane(u / per);
+      cur.r = u - cur.hh * per;
       cur.row0 = cursor_row0(cur);
       return cur;
     };
     // -> true when the new tile is the one right after the old one in the same head
     auto cursor_next = [&](Cursor& cur) {
-      if (cur.seq + 1 >= total) return false;
+      if (cur.seq + 1 >= seq_hi) return false;
       ++cur.seq;
       ++cur.r;
       if (cur.r == (cur.unmasked ? nu : nm)) {
@@ -624,13 +640,16 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     dma.init(gtid);
     const unsigned smem_lds = lds_addr(smem);
     const int gwave_u = wave_u & (NW / 2 - 1);
-    struct CopyJob { const bf16_t* src; unsigned dst; uint32_t row_bytes; int rows; const float* stat_src; unsigned stat_dst; };
+    struct CopyJob { const bf16_t* src; unsigned dst; uint32_t row_bytes; int rows; const float* stat_src; uint32_t stat_off; unsigned stat_dst; };
     // this group's operand: Q (group A, with the row statistics) or dO (group B)
     const bool copies_q = !group_b;
     const bf16_t* const src_base = copies_q ? a.q + (int64_t)b * a.q_stride_b : a.d_out + (int64_t)b * a.do_stride_b;
     const int64_t src_stride_h = copies_q ? a.q_stride_h : a.do_stride_h;
     const int64_t src_stride_s = copies_q ? a.q_stride_s : a.do_stride_s;
-    const float* const stat_base = a.lse2 + (int64_t)b * a.n_q_heads * a.s_q + (g ? stat_gap : 0);
+    // lanes 0..31 read lse2, lanes 32..63 delta: one uniform base (the lower array) + a 32-bit lane offset
+    // (the workspace is far below 4 GB)
+    const float* const stat_base = (stat_gap < 0 ? a.delta : a.lse2) + (int64_t)b * a.n_q_heads * a.s_q;
+    const uint32_t stat_off_lse2 = stat_gap < 0 ? (uint32_t)(-stat_gap) * 4u : 0u, stat_off_delta = stat_gap < 0 ? 0u : (uint32_t)stat_gap * 4u;
     const uint32_t src_row_bytes = (uint32_t)src_stride_s * 2;
     const int64_t src_tile_step = src_stride_s * BMQ;
     // global addresses of the tile at the copy cursor: the tile's first row of Q / dO and of the statistics
@@ -638,8 +657,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     auto src_at = [&](const Cursor& cc) {
       const int h = hk * a.group + cc.hh;
       CopySrc p;
-      p.tile = src_base + h * src_stride_h + cc.row0 * src_stride_s;
-      p.stat = stat_base + (int64_t)h * a.s_q + cc.row0;
+      p.tile = uniform_ptr(src_base + h * src_stride_h + cc.row0 * src_stride_s);
+      p.stat = uniform_ptr(stat_base + (int64_t)h * a.s_q + cc.row0);
       return p;
     };
     auto src_step = [&](CopySrc& p, const Cursor& cc, bool follows) {
@@ -655,8 +674,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
       j.dst = smem_lds + (copies_q ? L::Q_BASE : L::DO_BASE) + slot * TILE_BYTES;
       j.rows = a.s_q - cc.row0;
       // lanes 0..31: lse2 of rows row0 .. row0+31, lanes 32..63: delta of the same rows (clamped to the slice)
-      const int rr = ql < j.rows ? ql : j.rows - 1;
-      j.stat_src = p.stat + rr;
+      const int t2 = fresh(tid), ql2 = t2 & 31, g2 = (t2 >> 5) & 1;
+      const int rr = ql2 < j.rows ? ql2 : j.rows - 1;
+      j.stat_src = p.stat;
+      j.stat_off = (g2 ? stat_off_delta : stat_off_lse2) + (uint32_t)rr * 4u;
       j.stat_dst = smem_lds + L::STAT_BASE + slot * L::STAT_BYTES;
       return j;
     };
@@ -664,7 +685,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     // every wave of group A writes the same 64 statistics (no branch in the phase: identical data)
     auto copy_part = [&](const CopyJob& j, bool with_stats, int part) {
       if (part < PASSES) copy_pass(j, part);
-      if (part == 3 && with_stats) dma4(j.stat_src, j.stat_dst);
+      if (part == 3 && with_stats) dma4(j.stat_src, j.stat_off, j.stat_dst);
     };
     auto copy_all = [&](const CopyJob& j, bool with_stats) {
       for (int part = 0; part < 4; ++part) copy_part(j, with_stats, part);
@@ -701,17 +722,19 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     };
     Cursor mc = cursor_begin();          // the tile of the vector phase
     auto vector_phase = [&](int u, const CopyJob& j) {
-      const bool need_mask = u < total_m;
+      const bool need_mask = seq_lo + u < total_m;
       int rmin_rel = 0, rmax_rel = 32;
       if (need_mask) {
-        const int64_t rl = rmin_abs - mc.row0;
+        // first row of the tile that sees this lane's key (worked out here, in the rare masked tiles,
+        // rather than kept in a register across the loop)
+        const int64_t rl = a.causal ? tile_key0 + wave_u * 32 + (fresh(tid) & 31) - a.q_offset - mc.row0 : 0;
         rmin_rel = rl < 0 ? 0 : (rl > 32 ? 32 : (int)rl);
         const int left = a.s_q - mc.row0;
         rmax_rel = left > 32 ? 32 : left;
       }
       cursor_next(mc);
       const float* stat = reinterpret_cast<const float*>(smem + L::STAT_BASE + (u % SLOTS) * L::STAT_BYTES);
-      dkdv_vector_phase<D>(st, stat, c, need_mask, rmin_rel, rmax_rel, g, [&](int part) { copy_part(j, copies_q, part); });
+      dkdv_vector_phase<D>(st, stat, c, need_mask, rmin_rel, rmax_rel, (fresh(tid) >> 5) & 1, [&](int part) { copy_part(j, copies_q, part); });
     };
 #ifdef SLIMPIPE_TRACE
     long long tr_v = 0, tr_b1 = 0, tr_m = 0, tr_w = 0, tr_b2 = 0, tr_t0 = clock64(), tr_w0 = wall_clock64(), tr_last = clock64();
@@ -727,12 +750,18 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     wait_async();
     phase_end();
     TR_MARK(tr_b2)
-    for (int u = 0; u + 1 < total; ++u) {
+    // (a fresh live range for K right in front of the loop: if the register allocator had to park part of
+    // it in scratch memory during the prologue, it comes back here and not inside the loop)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(st.kreg[ks]));
+    for (int u = 0; u + 1 < cnt; ++u) {
       vector_phase(u, make_copy(cc, cp, u + 2));         // tile u+2 rides along
       src_step(cp, cc, cursor_next(cc));
       TR_MARK(tr_v)
       phase_end();
       TR_MARK(tr_b1)
+      // (V never moves: without this the eight offsets of its head_dim blocks are kept in registers across the loop)
+      asm volatile("" : "+v"(lo_v.off0));
       { DkdvMatrixPhase<D, NW, true, true, 2> ph{smem, lo_qt, lo_q, lo_v, st}; ph.run(); }    // sums of tile u, scores of tile u+1
       advance();
       TR_MARK(tr_m)
@@ -741,7 +770,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
       phase_end();
       TR_MARK(tr_b2)
     }
-    vector_phase(total - 1, make_copy(cc, cp, total + 1));   // (the last tile once more)
+    vector_phase(cnt - 1, make_copy(cc, cp, cnt + 1));   // (the last tile once more)
     phase_end();
     { DkdvMatrixPhase<D, NW, true, false, 2> ph{smem, lo_qt, lo_q, lo_v, st}; ph.run(); }     // sums of the last tile
     wait_async();
@@ -751,28 +780,75 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {
       long long* dbg = reinterpret_cast<long long*>(a.lse2 + (int64_t)a.n_q_heads * a.s_q);   // behind the workspace proper
       dbg[0] = tr_v; dbg[1] = tr_b1; dbg[2] = tr_m; dbg[3] = tr_w; dbg[4] = tr_b2;
-      dbg[5] = clock64() - tr_t0; dbg[6] = wall_clock64() - tr_w0; dbg[7] = total;
+      dbg[5] = clock64() - tr_t0; dbg[6] = wall_clock64() - tr_w0; dbg[7] = cnt;
     }
 #endif
   }
 
-  if (mykey < a.kv_end) {
-    const int64_t base = (int64_t)b * a.kv_stride_b + mykey * a.kv_stride_s + (int64_t)hk * a.kv_stride_h;
+  // (the key is worked out afresh from an opaque copy of the lane number: otherwise its 64 bits stay in
+  // registers across the whole loop, and registers are what this kernel is short of)
+  const int tid_out = fresh(tid), ql_out = tid_out & 31, g_out = (tid_out >> 5) & 1;
+  const int64_t mykey_out = tile_key0 + wave_u * 32 + ql_out;
+  if (mykey_out < a.kv_end) {
+    // one chunk: straight into the accumulators; several: this chunk's partial sums, added up in a
+    // fixed order by the reduce kernel
+    float* kdst;
+    float* vdst;
+    bool accumulate;
+    if (a.n_split > 1) {
+      const int64_t plane = (int64_t)gridDim.z * gridDim.y * a.nkeys_pad * D;          // one of dk / dv of one chunk
+      const int64_t row = (((int64_t)b * gridDim.y + hk) * a.nkeys_pad + (mykey_out - a.kv_begin)) * D;
+      kdst = a.part + (int64_t)split * 2 * plane + row;
+      vdst = kdst + plane;
+      accumulate = false;
+    } else {
+      const int64_t base = (int64_t)b * a.kv_stride_b + mykey_out * a.kv_stride_s + (int64_t)hk * a.kv_stride_h;
+      kdst = a.dk_acc + base;
+      vdst = a.dv_acc + base;
+      accumulate = a.dkv_accumulate != 0;
+    }
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        const int d = 32 * db + 8 * i4 + 4 * g;
+        const int d = 32 * db + 8 * i4 + 4 * g_out;
         f32x4 k4 = {st.dk[db][4 * i4] * a.scale, st.dk[db][4 * i4 + 1] * a.scale, st.dk[db][4 * i4 + 2] * a.scale,
                     st.dk[db][4 * i4 + 3] * a.scale};
         f32x4 v4 = {st.dv[db][4 * i4], st.dv[db][4 * i4 + 1], st.dv[db][4 * i4 + 2], st.dv[db][4 * i4 + 3]};
-        f32x4* kd = reinterpret_cast<f32x4*>(a.dk_acc + base + d);
-        f32x4* vd = reinterpret_cast<f32x4*>(a.dv_acc + base + d);
-        if (a.dkv_accumulate) { k4 += *kd; v4 += *vd; }
+        f32x4* kd = reinterpret_cast<f32x4*>(kdst + d);
+        f32x4* vd = reinterpret_cast<f32x4*>(vdst + d);
+        if (accumulate) { k4 += *kd; v4 += *vd; }
         *kd = k4;
         *vd = v4;
       }
   }
+}
+
+// dk_acc, dv_acc (+)= the partial sums of the chunks, chunk 0 first.
+__global__ __launch_bounds__(256) void dkdv_reduce_kernel(const BwdArgs a, int batch, int head_dim) {
+  const int64_t nkeys = a.kv_end - a.kv_begin;
+  const int dvec = head_dim / 4;
+  const int64_t total = (int64_t)batch * a.n_kv_heads * nkeys * dvec;
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (gid >= total) return;
+  const int d = (int)(gid % dvec) * 4;
+  const int64_t key = (gid / dvec) % nkeys;
+  const int64_t bh = gid / dvec / nkeys;
+  const int hk = (int)(bh % a.n_kv_heads), b = (int)(bh / a.n_kv_heads);
+  const int64_t plane = (int64_t)batch * a.n_kv_heads * a.nkeys_pad * head_dim;
+  const float* src = a.part + (bh * a.nkeys_pad + key) * head_dim + d;
+  f32x4 k4 = *reinterpret_cast<const f32x4*>(src);
+  f32x4 v4 = *reinterpret_cast<const f32x4*>(src + plane);
+  for (int s = 1; s < a.n_split; ++s) {
+    k4 += *reinterpret_cast<const f32x4*>(src + (int64_t)s * 2 * plane);
+    v4 += *reinterpret_cast<const f32x4*>(src + (int64_t)s * 2 * plane + plane);
+  }
+  const int64_t base = (int64_t)b * a.kv_stride_b + (a.kv_begin + key) * a.kv_stride_s + (int64_t)hk * a.kv_stride_h + d;
+  f32x4* kd = reinterpret_cast<f32x4*>(a.dk_acc + base);
+  f32x4* vd = reinterpret_cast<f32x4*>(a.dv_acc + base);
+  if (a.dkv_accumulate) { k4 += *kd; v4 += *vd; }
+  *kd = k4;
+  *vd = v4;
 }
 
 template <int D, int NW>
@@ -788,7 +864,7 @@ static hipError_t launch_dkdv_t(const BwdArgs& a, int batch, hipStream_t st) {
   }
   const int64_t nkeys = a.kv_end - a.kv_begin;
   if (nkeys <= 0) return hipSuccess;
-  dim3 grid((unsigned)((nkeys + BNK - 1) / BNK), a.n_kv_heads, batch), block(NW * 64);
+  dim3 grid((unsigned)((nkeys + BNK - 1) / BNK) * (unsigned)a.n_split, a.n_kv_heads, batch), block(NW * 64);
   hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, NW>), grid, block, smem, st, a);
   return hipGetLastError();
 }
@@ -797,5 +873,15 @@ hipError_t launch_bwd_dkdv(const BwdArgs& a, int batch, int head_dim, hipStream_
   if (head_dim == 128) return launch_dkdv_t<128, 8>(a, batch, st);
   return launch_dkdv_t<64, 8>(a, batch, st);
 }
+
+hipError_t launch_dkdv_reduce(const BwdArgs& a, int batch, int head_dim, hipStream_t st) {
+  const int64_t nkeys = a.kv_end - a.kv_begin;
+  if (nkeys <= 0 || a.n_split <= 1) return hipSuccess;
+  const int64_t total = (int64_t)batch * a.n_kv_heads * nkeys * (head_dim / 4);
+  hipLaunchKernelGGL(dkdv_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a, batch, head_dim);
+  return hipGetLastError();
+}
+
+int dkdv_keys_per_workgroup() { return 8 * 32; }
 
 }  // namespace slimpipe

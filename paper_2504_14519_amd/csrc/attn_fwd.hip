@@ -37,13 +37,14 @@ template <int D, int BN>
 SP_DEV float fwd_rowmax_first(FwdState<D, BN>& st, bool need_mask, int kmax_rel, int g) {
   constexpr int KB = BN / 32;
   if (need_mask) {
+    // key (kb*32 + 8*(i/4) + 4g + i%4) <= kmax_rel, with the lane's part on the right: the left side is an
+    // immediate (a register per element otherwise, hoisted out of the tile loop)
+    const int kmax_lane = kmax_rel - 4 * g;
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key_rel = kb * 32 + 8 * (i >> 2) + 4 * g + (i & 3);
-        st.s[kb][i] = key_rel <= kmax_rel ? st.s[kb][i] : -INFINITY;
-      }
+      for (int i = 0; i < 16; ++i)
+        st.s[kb][i] = (kb * 32 + 8 * (i >> 2) + (i & 3)) <= kmax_lane ? st.s[kb][i] : -INFINITY;
   }
   float mx = -INFINITY;
 #pragma unroll

@@ -31,6 +31,9 @@ struct BwdArgs {
   void* dq;
   float* dk_acc;
   float* dv_acc;
+  float* part;             // workspace [n_split][2][batch][n_kv_heads][nkeys_pad][head_dim]: partial dk, dv (n_split > 1)
+  int32_t n_split;         // chunks the query stream of a key tile is cut into (one workgroup each)
+  int64_t nkeys_pad;       // key rows per (batch, kv head) plane of `part`
   int32_t s_q, n_q_heads, n_kv_heads, group, causal;
   int32_t dq_f32, dq_accumulate, dkv_accumulate;
   int64_t q_offset, kv_begin, kv_end, kv_capacity;
@@ -54,6 +57,8 @@ hipError_t launch_fwd(const FwdArgs& a, int batch, int head_dim, hipStream_t st)
 hipError_t launch_delta(const BwdArgs& a, int batch, int head_dim, hipStream_t st);
 hipError_t launch_bwd_dq(const BwdArgs& a, int batch, int head_dim, hipStream_t st);
 hipError_t launch_bwd_dkdv(const BwdArgs& a, int batch, int head_dim, hipStream_t st);
+hipError_t launch_dkdv_reduce(const BwdArgs& a, int batch, int head_dim, hipStream_t st);
+int dkdv_keys_per_workgroup();
 hipError_t launch_merge(const MergeArgs& a, hipStream_t st);
 hipError_t launch_finalize(const float* acc, __bf16* dst, int64_t n, hipStream_t st);
 

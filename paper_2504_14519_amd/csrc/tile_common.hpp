@@ -184,16 +184,31 @@ SP_DEV bf16x8 lds_tr(const char* smem, const TrBase<D>& lo, int db, int const_of
 // LDS byte address of a pointer into shared memory (uniform).  Kernels take it once for the start of
 // their dynamic shared memory and do integer arithmetic from there: every cast of a generic pointer
 // costs a null check and a scalar read-back.
+// An opaque copy of a value: what is computed from it is computed afresh at this point instead of
+// being kept in a register from wherever the compiler first saw it (kernels at the register limit
+// derive lane-dependent quantities from the thread index where they need them).
+SP_DEV int fresh(int x) {
+  asm volatile("" : "+v"(x));
+  return x;
+}
+// A pointer the program knows to be the same in all lanes, read back into scalar registers (for
+// values that went through vector instructions on the way, e.g. an integer division).
+template <class T>
+SP_DEV T* uniform_ptr(T* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return reinterpret_cast<T*>(((uint64_t)hi << 32) | lo);
+}
 SP_DEV unsigned lds_addr(const void* p) {
   return __builtin_amdgcn_readfirstlane(
       (unsigned)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const char*)p));
 }
 // one dword per lane: lane i lands at lds_base + 4*i
-SP_DEV void dma4(const void* src, unsigned lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
-               :: "v"(src), "s"(lds_base) : "memory", "m0");
+SP_DEV void dma4(const void* base, uint32_t lane_off, unsigned lds_base) {      // base uniform, lane_off in bytes
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+               :: "v"(lane_off), "s"(base), "s"(lds_base) : "memory", "m0");
 }
-// A tile copy with nothing but two per-lane constants: THREADS/NC rows per pass with THREADS a
+// A tile copy with nothing but two per-lane constants (packed into one register): THREADS/NC rows per pass with THREADS a
 // multiple of 16*NC (THREADS = 256, NC = 16: 16 rows per pass), so pass n handles row
 // r0 + (THREADS/NC)*n of the tile and, the row step being a multiple of 16, the SAME swizzled chunk.
 // A tile copy is "uniform base + 32-bit lane offset" with the row clamped to the rows that exist
@@ -202,23 +217,21 @@ template <int D, int ROWS, int THREADS>
 struct TileDma {
   static constexpr int NC = D / 8, RPP = THREADS / NC, PASSES = ROWS / RPP;
   static_assert(RPP % 16 == 0 && ROWS % RPP == 0, "row step keeps the swizzle phase");
-  int r0;            // row of this lane in pass 0
-  uint32_t c16;      // byte offset of this lane's (swizzled) chunk inside the row
+  uint32_t rc;       // this lane's row in pass 0 (low half) and the byte offset of its swizzled chunk inside the row (high half)
   SP_DEV void init(int tid) {
     const int r = tid / NC, p = tid % NC;
     int c;
     if constexpr (D == 128) c = ((((p >> 2) ^ r) & 3) << 2) | (((p & 3) ^ (r >> 2)) & 3);
     else c = (p ^ r) & (NC - 1);
-    r0 = r;
-    c16 = (uint32_t)c * 16;
+    rc = (uint32_t)r | ((uint32_t)c * 16 << 16);
   }
   // pass n of the tile whose first row starts at `tile_base` (uniform) into the LDS tile at byte address
   // `lds_tile` (uniform); `wave` is the uniform index of the calling wave among the THREADS/64 that copy
   SP_DEV void issue(unsigned lds_tile, const bf16_t* tile_base, uint32_t row_bytes, int rows_avail, int wave, int n) const {
     const unsigned lds = lds_tile + (n * THREADS + wave * 64) * 16;
-    int r = r0 + RPP * n;
+    int r = (int)(rc & 0xffffu) + RPP * n;
     r = r < rows_avail ? r : rows_avail - 1;
-    const uint32_t off = (uint32_t)r * row_bytes + c16;
+    const uint32_t off = (uint32_t)r * row_bytes + (rc >> 16);
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :: "v"(off), "s"(tile_base), "s"(lds) : "memory", "m0");
   }
