@@ -211,7 +211,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
   const int m0 = qblk * BM, wrow0 = m0 + wave_u * 32;
   const int myrow = wrow0 + ql;
   const int myrow_c = myrow < a.s_q ? myrow : a.s_q - 1;
-  const int64_t qpos = a.q_offset + myrow;
 
   DqState<D, BN> st;
   {
@@ -266,11 +265,18 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
     auto vector_phase = [&](int u, const CopyJob& j) {
       const int64_t key0 = key0_of(u);
       const bool need_mask = (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
-      int64_t kmax = a.kv_end - 1;
-      if (a.causal && qpos < kmax) kmax = qpos;
-      kmax -= key0;
-      const int kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
-      dq_vector_phase<D, BN>(st, c, need_mask, kmax_rel, g, [&](int part) { if (part < PASSES) copy_pass(j, part); });
+      // last visible key of this lane's query relative to the tile: worked out in the masked tiles only, from
+      // the thread index (nothing lane-dependent is kept in registers across the loop for it)
+      const int t2 = fresh(tid);
+      int kmax_rel = BN;
+      if (need_mask) {
+        const int64_t qpos = a.q_offset + wrow0 + (t2 & 31);
+        int64_t kmax = a.kv_end - 1;
+        if (a.causal && qpos < kmax) kmax = qpos;
+        kmax -= key0;
+        kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
+      }
+      dq_vector_phase<D, BN>(st, c, need_mask, kmax_rel, (t2 >> 5) & 1, [&](int part) { if (part < PASSES) copy_pass(j, part); });
     };
 
     // prologue: the dO rows of the block (all threads), K(0), K(1) (group A), V(0), V(1) (group B)
@@ -346,13 +352,14 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
 #endif
   }
 
-  if (myrow < a.s_q) {
-    const int64_t base = (int64_t)b * a.q_stride_b + (int64_t)myrow * a.q_stride_s + (int64_t)h * a.q_stride_h;
+  const int tid_out = fresh(tid), myrow_out = wrow0 + (tid_out & 31), g_out = (tid_out >> 5) & 1;
+  if (myrow_out < a.s_q) {
+    const int64_t base = (int64_t)b * a.q_stride_b + (int64_t)myrow_out * a.q_stride_s + (int64_t)h * a.q_stride_h;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        const int d = 32 * db + 8 * i4 + 4 * g;
+        const int d = 32 * db + 8 * i4 + 4 * g_out;
         f32x4 v4 = {st.dq[db][4 * i4] * a.scale, st.dq[db][4 * i4 + 1] * a.scale, st.dq[db][4 * i4 + 2] * a.scale,
                     st.dq[db][4 * i4 + 3] * a.scale};
         if (a.dq_f32) {

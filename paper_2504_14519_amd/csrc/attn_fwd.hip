@@ -206,7 +206,6 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
   const int m0 = qblk * BM, wrow0 = m0 + wave_u * 32;
   const int myrow = wrow0 + ql;
   const int myrow_c = myrow < a.s_q ? myrow : a.s_q - 1;
-  const int64_t qpos = a.q_offset + myrow;
 
   FwdState<D, BN> st;
   {
@@ -274,11 +273,16 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
     auto rowmax_tile = [&](int t) {
       const int64_t key0 = key0_of(t);
       const bool need_mask = (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
-      int64_t kmax = a.kv_end - 1;
-      if (a.causal && qpos < kmax) kmax = qpos;
-      kmax -= key0;
-      const int kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
-      st.mx = fwd_rowmax_first<D, BN>(st, need_mask, kmax_rel, g);
+      const int t2 = fresh(tid);
+      int kmax_rel = BN;
+      if (need_mask) {       // last visible key of this lane's query relative to the tile
+        const int64_t qpos = a.q_offset + wrow0 + (t2 & 31);
+        int64_t kmax = a.kv_end - 1;
+        if (a.causal && qpos < kmax) kmax = qpos;
+        kmax -= key0;
+        kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
+      }
+      st.mx = fwd_rowmax_first<D, BN>(st, need_mask, kmax_rel, (t2 >> 5) & 1);
       asm volatile("" : "+v"(st.mx));      // keep it on this side of the phase barrier
     };
 

@@ -229,9 +229,12 @@ struct TileDma {
   // `lds_tile` (uniform); `wave` is the uniform index of the calling wave among the THREADS/64 that copy
   SP_DEV void issue(unsigned lds_tile, const bf16_t* tile_base, uint32_t row_bytes, int rows_avail, int wave, int n) const {
     const unsigned lds = lds_tile + (n * THREADS + wave * 64) * 16;
-    int r = (int)(rc & 0xffffu) + RPP * n;
+    // (from an opaque copy: the row of every pass would otherwise be kept in a register of its own
+    // across the caller's loop)
+    const uint32_t rcv = (uint32_t)fresh((int)rc);
+    int r = (int)(rcv & 0xffffu) + RPP * n;
     r = r < rows_avail ? r : rows_avail - 1;
-    const uint32_t off = (uint32_t)r * row_bytes + (rc >> 16);
+    const uint32_t off = (uint32_t)r * row_bytes + (rcv >> 16);
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :: "v"(off), "s"(tile_base), "s"(lds) : "memory", "m0");
   }
