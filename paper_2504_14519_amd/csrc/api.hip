@@ -1,6 +1,5 @@
 // C ABI of the library: host-only validation, launch planning, error mapping.
 #include <math.h>
-#include <stdlib.h>
 #include <string.h>
 
 #include <vector>
@@ -207,7 +206,6 @@ int slimpipe_attn_bwd(const slimpipe_attn_params* p, const void* q_slice, const 
   a.lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + stat_bytes(p));
   a.dq = dq; a.dk_acc = dk_acc; a.dv_acc = dv_acc;
   int split = preferred_split(p);
-  if (const char* e = getenv("SLIMPIPE_EXP_SPLIT")) split = atoi(e);
   while (split > 1 && delta_bytes(p) + split_bytes(p, split) > workspace_bytes) split /= 2;
   a.n_split = split;
   a.part = reinterpret_cast<float*>(static_cast<char*>(workspace) + delta_bytes(p));

@@ -197,3 +197,43 @@ def test_dkdv_bit_reproducible(sp):
         res.append((dk_acc.cpu(), dv_acc.cpu(), dq.cpu()))
     for r in res[1:]:
         assert torch.equal(r[0], res[0][0]) and torch.equal(r[1], res[0][1]) and torch.equal(r[2], res[0][2])
+
+
+def test_dkdv_split_query_stream(sp):
+    """Few key tiles and a long query stream: the dk/dv kernel cuts the stream of every key tile into
+    chunks (partial sums + reduce kernel).  Checked against the oracle, against the unsplit path
+    (workspace too small for partial sums) and for bit-reproducibility, with and without accumulation."""
+    import torch
+    B, s, Hq, Hkv, D, Nkv, q_off = 1, 2048, 4, 2, 128, 2304, 256
+    scale = 1.0 / math.sqrt(D)
+    qb, kb, vb, dob = normal_bf16((B, s, Hq, D), 9, "q"), normal_bf16((B, Nkv, Hkv, D), 9, "k"), normal_bf16((B, Nkv, Hkv, D), 9, "v"), normal_bf16((B, s, Hq, D), 9, "do")
+    q64, k64, v64, do64 = (bf16_bits_to_f64(x) for x in (qb, kb, vb, dob))
+    q, k, v, do = dev_bf16(qb), dev_bf16(kb), dev_bf16(vb), dev_bf16(dob)
+    kv_end = q_off + s - 100            # ragged end: the last key tile is partial, the last rows see all keys
+    p = sp.make_params(q, k, q, q_off, 0, kv_end, True, scale)
+    need = sp.slimpipe_attn_workspace_bytes(p, True)
+    stats_only = 2 * (((B * Hq * s * 4) + 255) // 256 * 256)
+    assert need > stats_only, "this shape is meant to ask for a split"
+    o, l = sp.slimpipe_attn_fwd(q, k, v, q_off, 0, kv_end, True, scale)
+    torch.cuda.synchronize()
+    o_ref, l_ref = attn_fwd(q64, k64, v64, q_off, 0, kv_end, True, scale)
+    dq_ref, dk_ref, dv_ref = attn_bwd(q64, k64, v64, host_f64(o), do64, host_f64(l), q_off, 0, kv_end, True, scale)
+    res = {}
+    for name, ws_bytes in (("split", need), ("split again", need), ("unsplit", stats_only)):
+        say("dk/dv %s: workspace %d bytes" % (name, ws_bytes))
+        ws = torch.empty(ws_bytes, device="cuda:0", dtype=torch.uint8)
+        dk_acc = torch.full((B, Nkv, Hkv, D), 0.5, device="cuda:0")
+        dv_acc = torch.full((B, Nkv, Hkv, D), -0.25, device="cuda:0")
+        sp.slimpipe_attn_bwd(q, k, v, o, do, l, q_off, 0, kv_end, dk_acc, dv_acc, True, scale, dq_dtype=sp.F32,
+                             dkv_accumulate=True, workspace=ws)
+        torch.cuda.synchronize()
+        res[name] = (dk_acc.cpu(), dv_acc.cpu())
+        dk_g, dv_g = host_f64(dk_acc), host_f64(dv_acc)
+        check_grad("dk (%s)" % name, dk_acc[:, :kv_end] - 0.5, dk_ref[:, :kv_end])
+        check_grad("dv (%s)" % name, dv_acc[:, :kv_end] + 0.25, dv_ref[:, :kv_end])
+        # rows outside [kv_begin, kv_end) are untouched
+        assert np.all(dk_g[:, kv_end:] == 0.5) and np.all(dv_g[:, kv_end:] == -0.25)
+    assert torch.equal(res["split"][0], res["split again"][0]) and torch.equal(res["split"][1], res["split again"][1])
+    # the split only changes the order of fp32 additions
+    assert torch.allclose(res["split"][0], res["unsplit"][0], rtol=1e-4, atol=1e-4)
+    assert torch.allclose(res["split"][1], res["unsplit"][1], rtol=1e-4, atol=1e-4)
