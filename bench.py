@@ -179,7 +179,7 @@ def cpu_baseline(cfg_id, c, s, scale):
     from oracle import attn_fwd, attn_bwd
     from synth_inputs import normal_bf16, bf16_bits_to_f64
     Hq, Hkv, D = c["Hq"], c["Hkv"], c["D"]
-    rows = min(s, 1024)
+    rows = min(s, 4096)                          # about 10-15 s of host work, a few GB of fp64 scores per head
     i = min(2, c["n"] - 1)                        # third slice: two cached slices + the diagonal block
     kv_end = i * s + rows
     rng_cfg = 15                                  # its own seed family: a sample, not the workload tensors
