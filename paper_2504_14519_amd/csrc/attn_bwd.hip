@@ -148,9 +148,12 @@ struct DqMatrixPhase {
   }
   SP_DEV void run() {
     SP_FENCE();
+    matrix_phase_begin();
     prologue<0>();
     SP_FENCE();
     step<0>();
+    matrix_phase_end();
+    SP_FENCE();
   }
 };
 
@@ -486,9 +489,12 @@ struct DkdvMatrixPhase {
   }
   SP_DEV void run() {
     SP_FENCE();
+    matrix_phase_begin();
     prologue<0>();
     SP_FENCE();
     step<0>();
+    matrix_phase_end();
+    SP_FENCE();
   }
 };
 
@@ -539,6 +545,8 @@ SP_DEV void dkdv_vector_phase(DkdvState<D>& st, const float* stat, float c, bool
     asm volatile("" : "+v"(st.pb[h]), "+v"(st.dsb[h]));
   }
 }
+
+static_assert((DkdvLds<128, 8>::SLOTS & (DkdvLds<128, 8>::SLOTS - 1)) == 0, "ring slots are stepped with a mask");
 
 template <int D, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a) {
@@ -599,45 +607,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
   const int cnt = seq_hi - seq_lo;
 
   if (cnt > 0) {
-    // Position in the stream of query tiles: masked tiles of head 0, 1, .. of the group, then the unmasked
-    // tiles of head 0, 1, ..  Stepping it is a few scalar additions when the next tile follows in the
-    // same head (no division, no 64-bit product: a wave issues in order and a chain of scalar
-    // operations holds up the vector work behind it); it stays on the last tile once it is there.
-    struct Cursor {
-      int seq, hh, r, row0;
-      bool unmasked;
-    };
-    auto cursor_row0 = [&](const Cursor& cur) {
-      const int qt = cur.unmasked ? qtm + cur.r : (cur.r < qtm - qt0 ? qt0 + cur.r : nqt - 1);
-      return qt * BMQ;
-    };
-    auto cursor_begin = [&]() {
-      Cursor cur;
-      cur.seq = seq_lo;
-      cur.unmasked = seq_lo >= total_m;
-      const int u = cur.unmasked ? seq_lo - total_m : seq_lo, per = cur.unmasked ? nu : nm;   // per > 0: the chunk is not empty
-      cur.hh = __builtin_amdgcn_readfirstlane(u / per);
-      cur.r = u - cur.hh * per;
-      cur.row0 = cursor_row0(cur);
-      return cur;
-    };
-    // -> true when the new tile is the one right after the old one in the same head
-    auto cursor_next = [&](Cursor& cur) {
-      if (cur.seq + 1 >= seq_hi) return false;
-      ++cur.seq;
-      ++cur.r;
-      if (cur.r == (cur.unmasked ? nu : nm)) {
-        cur.r = 0;
-        ++cur.hh;
-        if (cur.hh == a.group) { cur.hh = 0; cur.unmasked = true; }
-        cur.row0 = cursor_row0(cur);
-        return false;
-      }
-      const int row0 = cursor_row0(cur);
-      const bool follows = row0 == cur.row0 + BMQ;
-      cur.row0 = row0;
-      return follows;
-    };
     // lse2 and delta are two arrays of one workspace; (a per-lane choice between the two pointers would
     // become a vector load of the kernel argument, and the wait for it would sit inside the loop)
     const int64_t stat_gap = a.delta - a.lse2;
@@ -647,7 +616,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     dma.init(gtid);
     const unsigned smem_lds = lds_addr(smem);
     const int gwave_u = wave_u & (NW / 2 - 1);
-    struct CopyJob { const bf16_t* src; unsigned dst; uint32_t row_bytes; int rows; const float* stat_src; uint32_t stat_off; unsigned stat_dst; };
     // this group's operand: Q (group A, with the row statistics) or dO (group B)
     const bool copies_q = !group_b;
     const bf16_t* const src_base = copies_q ? a.q + (int64_t)b * a.q_stride_b : a.d_out + (int64_t)b * a.do_stride_b;
@@ -659,31 +627,75 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     const uint32_t stat_off_lse2 = stat_gap < 0 ? (uint32_t)(-stat_gap) * 4u : 0u, stat_off_delta = stat_gap < 0 ? 0u : (uint32_t)stat_gap * 4u;
     const uint32_t src_row_bytes = (uint32_t)src_stride_s * 2;
     const int64_t src_tile_step = src_stride_s * BMQ;
-    // global addresses of the tile at the copy cursor: the tile's first row of Q / dO and of the statistics
-    struct CopySrc { const bf16_t* tile; const float* stat; };
-    auto src_at = [&](const Cursor& cc) {
-      const int h = hk * a.group + cc.hh;
-      CopySrc p;
-      p.tile = uniform_ptr(src_base + h * src_stride_h + cc.row0 * src_stride_s);
-      p.stat = uniform_ptr(stat_base + (int64_t)h * a.s_q + cc.row0);
-      return p;
+
+    // Copy cursor over the stream of query tiles: masked tiles of head 0, 1, .. of the group, then the
+    // unmasked tiles of head 0, 1, ..  The stream is a sequence of RUNS of tiles that follow each other in
+    // one head; inside a run a step is a decrement and three additions, and only the start of a run
+    // costs products and selects.  (A wave issues in order: every scalar instruction of the vector
+    // phase, of which the first version of this cursor had a hundred per tile, delays the vector work
+    // behind it.)  It stays on the last tile of the chunk once it is there.
+    struct Cursor {
+      int seq;               // index of the tile in the stream
+      int run_left;          // tiles of the current run from this one on (cut at the end of the chunk)
+      int run_len;           // tiles of the current run from its first tile of this chunk on
+      int hh, r;             // head within the group, index of the run's first tile in the head's masked / unmasked list
+      bool unmasked;
+      int row0;              // first query row of the tile
+      const bf16_t* tile;    // global address of its first row of Q / dO
+      const float* stat;     // and of its first row statistic
     };
-    auto src_step = [&](CopySrc& p, const Cursor& cc, bool follows) {
-      if (follows) { p.tile += src_tile_step; p.stat += BMQ; }
-      else p = src_at(cc);
+    auto run_start = [&](Cursor& cur) {
+      int qt, len;
+      if (cur.unmasked) { qt = qtm + cur.r; len = nu - cur.r; }
+      else if (cur.r < qtm - qt0) { qt = qt0 + cur.r; len = (qtm - qt0) - cur.r; }
+      else { qt = nqt - 1; len = 1; }                      // the partial last tile of the slice
+      const int room = seq_hi - cur.seq;
+      cur.run_left = cur.run_len = len < room ? len : room;
+      cur.row0 = qt * BMQ;
+      const int h = hk * a.group + cur.hh;
+      cur.tile = uniform_ptr(src_base + h * src_stride_h + cur.row0 * src_stride_s);
+      cur.stat = uniform_ptr(stat_base + (int64_t)h * a.s_q + cur.row0);
     };
-    // tile t of the stream (at the copy cursor `cc`, addresses `p`) into ring slot t % SLOTS
-    auto make_copy = [&](const Cursor& cc, const CopySrc& p, int t) {
-      const int slot = t % SLOTS;
+    auto cursor_begin = [&]() {
+      Cursor cur;
+      cur.seq = seq_lo;
+      cur.unmasked = seq_lo >= total_m;
+      const int u = cur.unmasked ? seq_lo - total_m : seq_lo, per = cur.unmasked ? nu : nm;   // per > 0: the chunk is not empty
+      cur.hh = __builtin_amdgcn_readfirstlane(u / per);
+      cur.r = u - cur.hh * per;
+      run_start(cur);
+      return cur;
+    };
+    auto cursor_next = [&](Cursor& cur) {
+      if (cur.run_left > 1) {
+        --cur.run_left;
+        ++cur.seq;
+        cur.row0 += BMQ;
+        cur.tile += src_tile_step;
+        cur.stat += BMQ;
+      } else if (cur.seq + 1 < seq_hi) {
+        ++cur.seq;
+        cur.r += cur.run_len;
+        if (cur.r == (cur.unmasked ? nu : nm)) {
+          cur.r = 0;
+          ++cur.hh;
+          if (cur.hh == a.group) { cur.hh = 0; cur.unmasked = true; }
+        }
+        run_start(cur);
+      }
+    };
+    struct CopyJob { const bf16_t* src; unsigned dst; uint32_t row_bytes; int rows; const float* stat_src; uint32_t stat_off; unsigned stat_dst; };
+    // the tile at the cursor into ring slot `slot`
+    auto make_copy = [&](const Cursor& cc, int slot) {
       CopyJob j;
-      j.src = p.tile;
+      j.src = cc.tile;
       j.row_bytes = src_row_bytes;
       j.dst = smem_lds + (copies_q ? L::Q_BASE : L::DO_BASE) + slot * TILE_BYTES;
       j.rows = a.s_q - cc.row0;
       // lanes 0..31: lse2 of rows row0 .. row0+31, lanes 32..63: delta of the same rows (clamped to the slice)
       const int t2 = fresh(tid), ql2 = t2 & 31, g2 = (t2 >> 5) & 1;
       const int rr = ql2 < j.rows ? ql2 : j.rows - 1;
-      j.stat_src = p.stat;
+      j.stat_src = cc.stat;
       j.stat_off = (g2 ? stat_off_delta : stat_off_lse2) + (uint32_t)rr * 4u;
       j.stat_dst = smem_lds + L::STAT_BASE + slot * L::STAT_BYTES;
       return j;
@@ -708,11 +720,13 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
         dma_v.issue(smem_lds + L::V_BASE, vbase, (uint32_t)a.kv_stride_s * 2, avail > BNK ? BNK : (int)avail, wave_u, n);
     }
     Cursor cc = cursor_begin();          // copy cursor: two tiles ahead of the tile being worked on
-    CopySrc cp = src_at(cc);
-    copy_all(make_copy(cc, cp, 0), copies_q);
-    src_step(cp, cc, cursor_next(cc));
-    copy_all(make_copy(cc, cp, 1), copies_q);
-    src_step(cp, cc, cursor_next(cc));
+    // first rows of the tile of the vector phase and of the one after it (the masks need them)
+    int row0_cur = cc.row0;
+    copy_all(make_copy(cc, 0), copies_q);
+    cursor_next(cc);
+    int row0_nxt = cc.row0;
+    copy_all(make_copy(cc, 1), copies_q);
+    cursor_next(cc);
     wait_async();
     TrBase<D> lo_qt;         // Q(u-1), transposed
     RpBase<D> lo_q, lo_v;    // Q(u) and this wave's V rows, row-packed
@@ -727,20 +741,19 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
       lo_qt.add(slot == 0 ? -(SLOTS - 1) * TILE_BYTES : TILE_BYTES);      // Q(u-1) sits in slot - 1
       slot = (slot == SLOTS - 1) ? 0 : slot + 1;
     };
-    Cursor mc = cursor_begin();          // the tile of the vector phase
-    auto vector_phase = [&](int u, const CopyJob& j) {
+    // vector phase of tile u (ring slot vslot, first row row0), with the copies of job j riding along
+    auto vector_phase = [&](int u, int vslot, int row0, const CopyJob& j) {
       const bool need_mask = seq_lo + u < total_m;
       int rmin_rel = 0, rmax_rel = 32;
       if (need_mask) {
         // first row of the tile that sees this lane's key (worked out here, in the rare masked tiles,
         // rather than kept in a register across the loop)
-        const int64_t rl = a.causal ? tile_key0 + wave_u * 32 + (fresh(tid) & 31) - a.q_offset - mc.row0 : 0;
+        const int64_t rl = a.causal ? tile_key0 + wave_u * 32 + (fresh(tid) & 31) - a.q_offset - row0 : 0;
         rmin_rel = rl < 0 ? 0 : (rl > 32 ? 32 : (int)rl);
-        const int left = a.s_q - mc.row0;
+        const int left = a.s_q - row0;
         rmax_rel = left > 32 ? 32 : left;
       }
-      cursor_next(mc);
-      const float* stat = reinterpret_cast<const float*>(smem + L::STAT_BASE + (u % SLOTS) * L::STAT_BYTES);
+      const float* stat = reinterpret_cast<const float*>(smem + L::STAT_BASE + vslot * L::STAT_BYTES);
       dkdv_vector_phase<D>(st, stat, c, need_mask, rmin_rel, rmax_rel, (fresh(tid) >> 5) & 1, [&](int part) { copy_part(j, copies_q, part); });
     };
 #ifdef SLIMPIPE_TRACE
@@ -761,9 +774,15 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     // it in scratch memory during the prologue, it comes back here and not inside the loop)
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(st.kreg[ks]));
+    int vslot = 0, cslot = 2;            // ring slots of the tile of the vector phase and of the tile being copied
     for (int u = 0; u + 1 < cnt; ++u) {
-      vector_phase(u, make_copy(cc, cp, u + 2));         // tile u+2 rides along
-      src_step(cp, cc, cursor_next(cc));
+      const int row0_new = cc.row0;
+      vector_phase(u, vslot, row0_cur, make_copy(cc, cslot));      // tile u+2 rides along
+      cursor_next(cc);
+      row0_cur = row0_nxt;
+      row0_nxt = row0_new;
+      vslot = (vslot + 1) & (SLOTS - 1);
+      cslot = (cslot + 1) & (SLOTS - 1);
       TR_MARK(tr_v)
       phase_end();
       TR_MARK(tr_b1)
@@ -777,7 +796,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
       phase_end();
       TR_MARK(tr_b2)
     }
-    vector_phase(cnt - 1, make_copy(cc, cp, cnt + 1));   // (the last tile once more)
+    vector_phase(cnt - 1, vslot, row0_cur, make_copy(cc, cslot));   // (copies the last tile once more)
     phase_end();
     { DkdvMatrixPhase<D, NW, true, false, 2> ph{smem, lo_qt, lo_q, lo_v, st}; ph.run(); }     // sums of the last tile
     wait_async();

@@ -183,9 +183,12 @@ struct FwdMatrixPhase {
   }
   SP_DEV void run() {
     SP_FENCE();
+    matrix_phase_begin();
     prologue<0>();
     SP_FENCE();
     step<0>();
+    matrix_phase_end();
+    SP_FENCE();
   }
 };
 
