@@ -96,7 +96,6 @@ struct DqMatrixPhase {
   static constexpr int KB = BN / 32, DB = D / 32, KS = D / 16;
   static constexpr int N_DQ = WITH_DQ ? 2 * KB * DB : 0, N_SC = WITH_SCORES ? 2 * KB * KS : 0, N = N_DQ + N_SC;
   static constexpr int NBUF = LOOK + 1;
-  const char* smem;
   const TrBase<D>& lo_kt;
   const RpBase<D>& lo_k;
   const RpBase<D>& lo_v;
@@ -109,14 +108,14 @@ struct DqMatrixPhase {
   SP_DEV void reads() {
     if constexpr (M < N_DQ) {
       constexpr int db = M % DB, blk = M / DB;                 // blk = 2*kb + half: 16 keys each
-      abuf[M % NBUF] = lds_tr<D>(smem, lo_kt, db, blk * 16 * D * 2);
+      abuf[M % NBUF] = lds_tr<D>(lo_kt, db, blk * 16 * D * 2);
     } else if constexpr (M < N) {
       constexpr int j = M - N_DQ, ks = j / (2 * KB), r = j % (2 * KB), kb = r / 2;
       if constexpr ((r & 1) == 0) {
-        abuf[M % NBUF] = lds_rp<D>(smem, lo_k, ks, kb * 32 * D * 2);
+        abuf[M % NBUF] = lds_rp<D>(lo_k, ks, kb * 32 * D * 2);
       } else {
-        abuf[M % NBUF] = lds_rp<D>(smem, lo_v, ks, kb * 32 * D * 2);
-        if constexpr (kb == 0) dob[ks & 1] = lds_rp<D>(smem, lo_do, ks, 0);
+        abuf[M % NBUF] = lds_rp<D>(lo_v, ks, kb * 32 * D * 2);
+        if constexpr (kb == 0) dob[ks & 1] = lds_rp<D>(lo_do, ks, 0);
       }
     }
   }
@@ -158,9 +157,9 @@ struct DqMatrixPhase {
 };
 
 template <int D, int BN, bool WITH_DQ, bool WITH_SCORES>
-SP_DEV void dq_matrix_phase(const char* smem, const TrBase<D>& lo_kt, const RpBase<D>& lo_k, const RpBase<D>& lo_v,
+SP_DEV void dq_matrix_phase(const TrBase<D>& lo_kt, const RpBase<D>& lo_k, const RpBase<D>& lo_v,
                             const RpBase<D>& lo_do, DqState<D, BN>& st) {
-  DqMatrixPhase<D, BN, WITH_DQ, WITH_SCORES, 2> ph{smem, lo_kt, lo_k, lo_v, lo_do, st};
+  DqMatrixPhase<D, BN, WITH_DQ, WITH_SCORES, 2> ph{lo_kt, lo_k, lo_v, lo_do, st};
   ph.run();
 }
 
@@ -203,7 +202,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
   constexpr int TILE_BYTES = BN * D * 2;
   constexpr int KSLOTS = 4, VSLOTS = 2;
   constexpr int K_BASE = 0, V_BASE = KSLOTS * TILE_BYTES, DO_BASE = (KSLOTS + VSLOTS) * TILE_BYTES;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ql = lane & 31;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);      // known uniform to the compiler
@@ -295,11 +294,11 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
     wait_async();
     TrBase<D> lo_kt;         // K(u-1), transposed
     RpBase<D> lo_k, lo_v;    // K(u), V(u), row-packed
-    lo_kt.init(lane, K_BASE + (KSLOTS - 1) * TILE_BYTES);      // "K(-1)": never read
-    lo_k.init(lane, K_BASE);
-    lo_v.init(lane, V_BASE);
+    lo_kt.init(lane, (int)smem_lds + K_BASE + (KSLOTS - 1) * TILE_BYTES);      // "K(-1)": never read
+    lo_k.init(lane, (int)smem_lds + K_BASE);
+    lo_v.init(lane, (int)smem_lds + V_BASE);
     RpBase<D> lo_do;         // this wave's 32 rows of dO
-    lo_do.init(lane, DO_BASE + wave * 32 * D * 2);
+    lo_do.init(lane, (int)smem_lds + DO_BASE + wave * 32 * D * 2);
     __syncthreads();
 
     // ring bookkeeping after matrix phase u: every pointer moves one tile on
@@ -322,7 +321,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
 #define TQ_MARK(var)
 #endif
     if (group_b) phase_end();
-    dq_matrix_phase<D, BN, false, true>(smem, lo_kt, lo_k, lo_v, lo_do, st);       // scores of tile 0
+    dq_matrix_phase<D, BN, false, true>(lo_kt, lo_k, lo_v, lo_do, st);       // scores of tile 0
     advance();
     wait_async();
     phase_end();
@@ -332,7 +331,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
       TQ_MARK(tq_v)
       phase_end();
       TQ_MARK(tq_b1)
-      dq_matrix_phase<D, BN, true, true>(smem, lo_kt, lo_k, lo_v, lo_do, st);      // dQ of tile u, scores of tile u+1
+      dq_matrix_phase<D, BN, true, true>(lo_kt, lo_k, lo_v, lo_do, st);      // dQ of tile u, scores of tile u+1
       advance();
       TQ_MARK(tq_m)
       wait_async();                                      // the copies of the vector phase before have landed
@@ -342,7 +341,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
     }
     vector_phase(nt - 1, make_copy(copies_k, nt + 1));   // (clamped: copies the last tile once more)
     phase_end();
-    dq_matrix_phase<D, BN, true, false>(smem, lo_kt, lo_k, lo_v, lo_do, st);       // dQ of the last tile
+    dq_matrix_phase<D, BN, true, false>(lo_kt, lo_k, lo_v, lo_do, st);       // dQ of the last tile
     wait_async();
     phase_end();
     if (!group_b) phase_end();
@@ -437,7 +436,6 @@ struct DkdvMatrixPhase {
   static constexpr int KS = D / 16, DB = D / 32;
   static constexpr int N_AC = WITH_ACC ? 4 * DB : 0, N_SC = WITH_SCORES ? 2 * KS : 0, N = N_AC + N_SC;
   static constexpr int NBUF = LOOK + 1, HALF = 16 * D * 2;
-  const char* smem;
   const TrBase<D>& lo_qt;      // Q(u-1), transposed; dO(u-1) sits DO_BASE further
   const RpBase<D>& lo_q;       // Q(u), row-packed; dO(u) sits DO_BASE further
   const RpBase<D>& lo_v;       // this wave's 32 rows of V
@@ -449,14 +447,14 @@ struct DkdvMatrixPhase {
   SP_DEV void reads() {
     if constexpr (M < N_AC) {
       constexpr int h = M / (2 * DB), db = (M % (2 * DB)) / 2;
-      abuf[M % NBUF] = lds_tr<D>(smem, lo_qt, db, ((M & 1) ? 0 : L::DO_BASE) + h * HALF);
+      abuf[M % NBUF] = lds_tr<D>(lo_qt, db, ((M & 1) ? 0 : L::DO_BASE) + h * HALF);
     } else if constexpr (M < N) {
       constexpr int j = M - N_AC, ks = j / 2;
       if constexpr ((j & 1) == 0) {
-        abuf[M % NBUF] = lds_rp<D>(smem, lo_q, ks, 0);
+        abuf[M % NBUF] = lds_rp<D>(lo_q, ks, 0);
       } else {
-        abuf[M % NBUF] = lds_rp<D>(smem, lo_q, ks, L::DO_BASE);
-        vb[ks & 1] = lds_rp<D>(smem, lo_v, ks, 0);
+        abuf[M % NBUF] = lds_rp<D>(lo_q, ks, L::DO_BASE);
+        vb[ks & 1] = lds_rp<D>(lo_v, ks, 0);
       }
     }
   }
@@ -554,7 +552,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
   using L = DkdvLds<D, NW>;
   constexpr int BNK = NW * 32, BMQ = L::BMQ, KS = D / 16, DB = D / 32, T = NW * 64, GT = T / 2;
   constexpr int TILE_BYTES = L::TILE_BYTES, SLOTS = L::SLOTS;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ql = lane & 31;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);      // known uniform to the compiler
@@ -730,9 +728,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     wait_async();
     TrBase<D> lo_qt;         // Q(u-1), transposed
     RpBase<D> lo_q, lo_v;    // Q(u) and this wave's V rows, row-packed
-    lo_qt.init(lane, L::Q_BASE + (SLOTS - 1) * TILE_BYTES);     // "Q(-1)": never read
-    lo_q.init(lane, L::Q_BASE);
-    lo_v.init(lane, L::V_BASE + wave_u * 32 * D * 2);
+    lo_qt.init(lane, (int)smem_lds + L::Q_BASE + (SLOTS - 1) * TILE_BYTES);     // "Q(-1)": never read
+    lo_q.init(lane, (int)smem_lds + L::Q_BASE);
+    lo_v.init(lane, (int)smem_lds + L::V_BASE + wave_u * 32 * D * 2);
     __syncthreads();
 
     int slot = 0;            // ring slot of tile u
@@ -765,7 +763,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     // Both groups run the same code; group B starts one phase (one barrier) later and group A idles
     // one phase at the end.
     if (group_b) phase_end();
-    { DkdvMatrixPhase<D, NW, false, true, 2> ph{smem, lo_qt, lo_q, lo_v, st}; ph.run(); }     // scores of tile 0
+    { DkdvMatrixPhase<D, NW, false, true, 2> ph{lo_qt, lo_q, lo_v, st}; ph.run(); }     // scores of tile 0
     advance();
     wait_async();
     phase_end();
@@ -788,7 +786,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
       TR_MARK(tr_b1)
       // (V never moves: without this the eight offsets of its head_dim blocks are kept in registers across the loop)
       asm volatile("" : "+v"(lo_v.off0));
-      { DkdvMatrixPhase<D, NW, true, true, 2> ph{smem, lo_qt, lo_q, lo_v, st}; ph.run(); }    // sums of tile u, scores of tile u+1
+      { DkdvMatrixPhase<D, NW, true, true, 2> ph{lo_qt, lo_q, lo_v, st}; ph.run(); }    // sums of tile u, scores of tile u+1
       advance();
       TR_MARK(tr_m)
       wait_async();                                      // the copies of the vector phase before have landed
@@ -798,7 +796,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     }
     vector_phase(cnt - 1, vslot, row0_cur, make_copy(cc, cslot));   // (copies the last tile once more)
     phase_end();
-    { DkdvMatrixPhase<D, NW, true, false, 2> ph{smem, lo_qt, lo_q, lo_v, st}; ph.run(); }     // sums of the last tile
+    { DkdvMatrixPhase<D, NW, true, false, 2> ph{lo_qt, lo_q, lo_v, st}; ph.run(); }     // sums of the last tile
     wait_async();
     phase_end();
     if (!group_b) phase_end();

@@ -140,7 +140,6 @@ struct FwdMatrixPhase {
   static constexpr int KB = BN / 32, DB = D / 32, KS = D / 16;
   static constexpr int N_PV = WITH_PV ? 2 * KB * DB : 0, N_S = WITH_S ? KB * KS : 0, N = N_PV + N_S;
   static constexpr int NBUF = LOOK + 1;
-  const char* smem;
   const TrOffsets<D>& lo_v;    // V(t-1), transposed
   const RpOffsets<D>& lo_k;    // K(t), row-packed
   FwdState<D, BN>& st;
@@ -150,10 +149,10 @@ struct FwdMatrixPhase {
   SP_DEV void reads() {
     if constexpr (M < N_PV) {
       constexpr int db = M % DB, blk = M / DB;                 // blk = 2*kb + half: 16 keys each
-      abuf[M % NBUF] = lds_tr<D>(smem, lo_v, db, blk * 16 * D * 2);
+      abuf[M % NBUF] = lds_tr<D>(lo_v, db, blk * 16 * D * 2);
     } else if constexpr (M < N) {
       constexpr int j = M - N_PV, ks = j / KB, kb = j % KB;
-      abuf[M % NBUF] = lds_rp<D>(smem, lo_k, ks, kb * 32 * D * 2);
+      abuf[M % NBUF] = lds_rp<D>(lo_k, ks, kb * 32 * D * 2);
     }
   }
   template <int M>
@@ -197,7 +196,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
   static_assert(NW == 8, "two groups of four waves");
   constexpr int BM = NW * 32, KS = D / 16, DB = D / 32, T = NW * 64;
   constexpr int TILE_BYTES = BN * D * 2;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
   constexpr int KSLOTS = 3, VSLOTS = 2;
   constexpr int K_BASE = 0, V_BASE = KSLOTS * TILE_BYTES;
 
@@ -296,8 +295,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
     wait_async();
     RpOffsets<D> lo_k;       // K(t), row-packed (registers are plentiful here: one offset per head_dim block)
     TrOffsets<D> lo_v;       // V(t-1), transposed
-    lo_k.init(lane, K_BASE);
-    lo_v.init(lane, V_BASE + TILE_BYTES);        // "V(-1)": never read
+    lo_k.init(lane, (int)smem_lds + K_BASE);
+    lo_v.init(lane, (int)smem_lds + V_BASE + TILE_BYTES);        // "V(-1)": never read
     __syncthreads();
 
     int kslot = 0, vslot = 1;       // slots of K(t) and V(t-1)
@@ -316,7 +315,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
     // Both groups run the same code; group B starts one phase (one barrier) later and group A idles
     // one phase at the end.
     if (group_b) phase_end();
-    { FwdMatrixPhase<D, BN, false, true, 2> ph{smem, lo_v, lo_k, st}; ph.run(); }
+    { FwdMatrixPhase<D, BN, false, true, 2> ph{lo_v, lo_k, st}; ph.run(); }
     rowmax_tile(0);
     advance();
     wait_async();
@@ -327,7 +326,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
       TP_MARK(tp_v)
       phase_end();
       TP_MARK(tp_b1)
-      { FwdMatrixPhase<D, BN, true, true, 2> ph{smem, lo_v, lo_k, st}; ph.run(); }
+      { FwdMatrixPhase<D, BN, true, true, 2> ph{lo_v, lo_k, st}; ph.run(); }
       rowmax_tile(t + 1);
       advance();
       TP_MARK(tp_m)
@@ -338,7 +337,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
     }
     vector_phase(copies_k ? make_copy(true, nt + 1) : make_copy(false, nt));
     phase_end();
-    { FwdMatrixPhase<D, BN, true, false, 2> ph{smem, lo_v, lo_k, st}; ph.run(); }
+    { FwdMatrixPhase<D, BN, true, false, 2> ph{lo_v, lo_k, st}; ph.run(); }
     wait_async();
     phase_end();
     if (!group_b) phase_end();

@@ -81,6 +81,15 @@ SP_DEV int tile_off(int row, int chunk) {
 //   columns 32*db + 16*(b&1) + 4*(j%4) .. +3 therefore hands lane l the column 32*db + (l&31) of rows
 //   row0 + 4g .. row0 + 4g+3; a second read 8 rows further completes the 8 k-slots of group g.
 //
+// The offsets below are LDS byte ADDRESSES (the kernel adds the address of its shared memory when it sets
+// them up): a read is "register + immediate" with no pointer arithmetic left.  (Through a pointer into
+// the shared array every read pays a vector add of the array's link-time address.)
+template <class T>
+SP_DEV T __attribute__((address_space(3))) * lds_ptr(int addr, int const_off) {
+  typedef char __attribute__((address_space(3))) * lds_char_ptr;
+  return reinterpret_cast<T __attribute__((address_space(3))) *>(reinterpret_cast<lds_char_ptr>(static_cast<uintptr_t>((unsigned)addr)) + const_off);
+}
+
 // Per-lane byte offsets of the two read patterns for a tile row block that starts at a multiple of
 // 16 rows.  Adding a multiple of 16 rows does not change the swizzle bits, so every read of a
 // kernel is (one of these registers) + (compile-time constant): the constant goes into the
@@ -118,17 +127,16 @@ struct TrOffsets {       // transposed: rows 4g + j/4 (+8 for the second read), 
   }
 };
 
-// Reads through the lane offsets; `smem` is the start of dynamic LDS, `const_off` a compile-time
-// byte offset (tile selector + 16-row block * row bytes).
+// Reads through the lane offsets; `const_off` is a compile-time byte offset (tile selector + 16-row
+// block * row bytes).
 template <int D>
-SP_DEV bf16x8 lds_rp(const char* smem, const RpOffsets<D>& lo, int ks, int const_off) {
-  return *reinterpret_cast<const bf16x8*>(smem + lo.off[ks] + const_off);
+SP_DEV bf16x8 lds_rp(const RpOffsets<D>& lo, int ks, int const_off) {
+  return *lds_ptr<bf16x8>(lo.off[ks], const_off);
 }
 template <int D>
-SP_DEV bf16x8 lds_tr(const char* smem, const TrOffsets<D>& lo, int db, int const_off) {
-  typedef bf16x4 __attribute__((address_space(3))) * lds_v4_ptr;
-  bf16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4_ptr)(smem + lo.off[db][0] + const_off));
-  bf16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4_ptr)(smem + lo.off[db][1] + const_off));
+SP_DEV bf16x8 lds_tr(const TrOffsets<D>& lo, int db, int const_off) {
+  bf16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(lds_ptr<bf16x4>(lo.off[db][0], const_off));
+  bf16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(lds_ptr<bf16x4>(lo.off[db][1], const_off));
   bf16x8 r;
   r[0] = a[0]; r[1] = a[1]; r[2] = a[2]; r[3] = a[3];
   r[4] = b[0]; r[5] = b[1]; r[6] = b[2]; r[7] = b[3];
@@ -155,16 +163,15 @@ struct TrBase {
   SP_DEV void add(int delta) { off0 += delta; }
 };
 template <int D>
-SP_DEV bf16x8 lds_rp(const char* smem, const RpBase<D>& lo, int ks, int const_off) {
-  return *reinterpret_cast<const bf16x8*>(smem + (lo.off0 ^ (32 * ks)) + const_off);
+SP_DEV bf16x8 lds_rp(const RpBase<D>& lo, int ks, int const_off) {
+  return *lds_ptr<bf16x8>(lo.off0 ^ (32 * ks), const_off);
 }
 template <int D>
-SP_DEV bf16x8 lds_tr(const char* smem, const TrBase<D>& lo, int db, int const_off) {
-  typedef bf16x4 __attribute__((address_space(3))) * lds_v4_ptr;
+SP_DEV bf16x8 lds_tr(const TrBase<D>& lo, int db, int const_off) {
   constexpr int X1 = D == 128 ? 32 : 0;       // rows +8 flip bit 1 of the swizzled chunk for D = 128
   const int o = lo.off0 ^ (64 * db);
-  bf16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4_ptr)(smem + o + const_off));
-  bf16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_v4_ptr)(smem + (o ^ X1) + 8 * D * 2 + const_off));
+  bf16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(lds_ptr<bf16x4>(o, const_off));
+  bf16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(lds_ptr<bf16x4>(o ^ X1, 8 * D * 2 + const_off));
   bf16x8 r;
   r[0] = a[0]; r[1] = a[1]; r[2] = a[2]; r[3] = a[3];
   r[4] = b[0]; r[5] = b[1]; r[6] = b[2]; r[7] = b[3];
