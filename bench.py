@@ -142,6 +142,12 @@ def main():
                           for kk in alg_flops if prof[kk][0] > 0},
     }
 
+    # what a pure stream of the same MFMA instruction sustains on this GPU (after the timed region): with
+    # random operands the chip is power limited, which is the regime the attention kernels run in
+    roofline["mfma_stream_tflops"] = {"constant_operands": round(sp.slimpipe_attn_mfma_rate(False), 1),
+                                      "random_operands": round(sp.slimpipe_attn_mfma_rate(True), 1)}
+    roofline["frac_of_mfma_stream_random"] = round(achieved / max(roofline["mfma_stream_tflops"]["random_operands"], 1e-9), 4)
+
     out = {
         "metric": "sliced causal attn fwd+bwd TFLOP/s and % of MI355X bf16 MFMA peak",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

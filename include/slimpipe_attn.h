@@ -138,6 +138,13 @@ enum {
 int slimpipe_attn_profile_enable(int enable);
 int slimpipe_attn_profile_read(double total_ms[SLIMPIPE_KERNEL_KINDS], int64_t launches[SLIMPIPE_KERNEL_KINDS]);
 
+/* Measurement aid for benchmarks (not part of the paper's method): the rate, in TFLOP/s, at which this
+ * GPU sustains a pure stream of the bf16 MFMA instruction the attention kernels use, with constant
+ * operands (random_operands == 0) or with random ones (!= 0), under which the chip is power limited
+ * and clocks lower.  Runs two short kernels (about 20 ms each) on the stream and waits for them.
+ * sink: device pointer to at least one float (never written in practice). */
+int slimpipe_attn_mfma_rate(int random_operands, float* sink, double* tflops, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -54,6 +54,8 @@ def _load():
     L.slimpipe_attn_merge.restype = ctypes.c_int
     L.slimpipe_attn_finalize_bf16.argtypes = [vp, vp, i64, vp]
     L.slimpipe_attn_finalize_bf16.restype = ctypes.c_int
+    L.slimpipe_attn_mfma_rate.argtypes = [ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double), vp]
+    L.slimpipe_attn_mfma_rate.restype = ctypes.c_int
     L.slimpipe_attn_profile_enable.argtypes = [ctypes.c_int]
     L.slimpipe_attn_profile_enable.restype = ctypes.c_int
     L.slimpipe_attn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
@@ -177,6 +179,15 @@ def slimpipe_attn_finalize_bf16(acc, dst=None):
 
 
 KERNEL_KINDS = ("fwd", "delta", "dq", "dkdv", "merge", "finalize", "dkdv_reduce")
+
+
+def slimpipe_attn_mfma_rate(random_operands):
+    """-> TFLOP/s of a pure bf16 MFMA stream on this GPU (constant or random operands)."""
+    import torch
+    sink = torch.zeros(4, device="cuda", dtype=torch.float32)
+    tf = ctypes.c_double(0.0)
+    _check(lib.slimpipe_attn_mfma_rate(1 if random_operands else 0, sink.data_ptr(), ctypes.byref(tf), _stream()), "mfma_rate")
+    return tf.value
 
 
 def slimpipe_attn_profile_enable(enable):

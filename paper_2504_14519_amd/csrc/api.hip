@@ -265,6 +265,26 @@ int slimpipe_attn_finalize_bf16(const float* acc, void* dst_bf16, int64_t n_elem
   return e == hipSuccess ? SLIMPIPE_OK : SLIMPIPE_ELAUNCH;
 }
 
+int slimpipe_attn_mfma_rate(int random_operands, float* sink, double* tflops, void* hip_stream) {
+  if (!sink || !tflops) return SLIMPIPE_EINVAL_NULL;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int iters = 20000, wgs = 8 * compute_units();
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return SLIMPIPE_ELAUNCH;
+  int rc = SLIMPIPE_OK;
+  float ms = 0.f;
+  // one untimed launch to get the clocks where they settle, then the timed one
+  if (launch_mfma_rate(random_operands, iters, wgs, sink, st) != hipSuccess) rc = SLIMPIPE_ELAUNCH;
+  if (rc == SLIMPIPE_OK && (hipEventRecord(e0, st) != hipSuccess || launch_mfma_rate(random_operands, iters, wgs, sink, st) != hipSuccess ||
+                            hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                            hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
+    rc = SLIMPIPE_ELAUNCH;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc == SLIMPIPE_OK) *tflops = (double)wgs * 8 * 4 * iters * 32768.0 / (ms * 1e-3) / 1e12;
+  return rc;
+}
+
 const char* slimpipe_attn_strerror(int code) {
   switch (code) {
     case SLIMPIPE_OK: return "ok";

@@ -93,4 +93,42 @@ hipError_t launch_finalize(const float* acc, __bf16* dst, int64_t n, hipStream_t
   return hipGetLastError();
 }
 
+// ---- measurement aid: what the matrix pipe sustains on this chip, outside any attention kernel ----
+// 8 waves per workgroup, every wave issues nothing but v_mfma_f32_32x32x16_bf16 on four accumulators.
+// With `random` operands (every bf16 a different hashed value in [2^-8, 1) with random sign) the chip
+// runs into its power limit and clocks down; with constant operands it does not: the two figures
+// bracket what "peak" means for a kernel that multiplies real data.
+__global__ __launch_bounds__(512) void mfma_rate_kernel(int random, int iters, float* sink) {
+  const unsigned tid = threadIdx.x + 512u * blockIdx.x;
+  bf16x8 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      unsigned ha = (tid * 64u + i * 16u + j) * 2654435761u, hb = (tid * 64u + i * 16u + 8u + j) * 2246822519u;
+      ha ^= ha >> 15; hb ^= hb >> 13;
+      // exponent 0x77..0x7e (2^-8 .. 2^-1), 7 random mantissa bits, random sign
+      const unsigned short ba = random ? (unsigned short)(((0x77u + (ha & 7u)) << 7) | ((ha >> 8) & 0x7fu) | ((ha >> 16) & 0x8000u)) : 0x3f00;
+      const unsigned short bb = random ? (unsigned short)(((0x77u + (hb & 7u)) << 7) | ((hb >> 8) & 0x7fu) | ((hb >> 16) & 0x8000u)) : 0x3f00;
+      a[i][j] = __builtin_bit_cast(bf16_t, ba);
+      b[i][j] = __builtin_bit_cast(bf16_t, bb);
+    }
+  f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+  for (int it = 0; it < iters; ++it) {
+    c0 = mfma32(a[0], b[0], c0);
+    c1 = mfma32(a[1], b[1], c1);
+    c2 = mfma32(a[2], b[2], c2);
+    c3 = mfma32(a[3], b[3], c3);
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) t += c0[i] + c1[i] + c2[i] + c3[i];
+  if (t == 12345.678f) sink[0] = t;          // keeps the loop alive; practically never true
+}
+
+hipError_t launch_mfma_rate(int random, int iters, int workgroups, float* sink, hipStream_t st) {
+  hipLaunchKernelGGL(mfma_rate_kernel, dim3((unsigned)workgroups), dim3(512), 0, st, random, iters, sink);
+  return hipGetLastError();
+}
+
 }  // namespace slimpipe

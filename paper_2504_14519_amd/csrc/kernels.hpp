@@ -61,5 +61,6 @@ hipError_t launch_dkdv_reduce(const BwdArgs& a, int batch, int head_dim, hipStre
 int dkdv_keys_per_workgroup();
 hipError_t launch_merge(const MergeArgs& a, hipStream_t st);
 hipError_t launch_finalize(const float* acc, __bf16* dst, int64_t n, hipStream_t st);
+hipError_t launch_mfma_rate(int random, int iters, int workgroups, float* sink, hipStream_t st);
 
 }  // namespace slimpipe
