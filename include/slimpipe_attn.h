@@ -125,6 +125,29 @@ int slimpipe_attn_merge(int32_t n_parts, const void* const* outs, const float* c
  * Contiguous, n_elems elements. */
 int slimpipe_attn_finalize_bf16(const float* acc, void* dst_bf16, int64_t n_elems, void* hip_stream);
 
+/* The same two calls with the cached keys / values given the way the paper stores them (Sec. 5): a list
+ * of slice-sized chunks instead of one buffer, so that the cache grows in the forward passes and shrinks
+ * in the backward passes without copies.
+ *   k_chunks, v_chunks (and dk_chunks, dv_chunks) : HOST arrays of n_chunks device pointers; row j of the
+ *              prefix is row j % chunk_len of chunk j / chunk_len, laid out inside the chunk with the kv
+ *              strides of `p` (kv_stride_s between rows).  The arrays are read during the call only.
+ *   n_chunks : 1 .. 64;  n_chunks * chunk_len >= p->kv_capacity;  with more than one chunk, chunk_len is a
+ *              multiple of 256 (SLIMPIPE_EINVAL_SHAPE otherwise).  Chunks of slices the range does not
+ *              touch are never dereferenced but must be non-NULL.
+ * Everything else (ranges, masks, outputs, workspace, accumulation, error codes) is as in the calls above;
+ * with one chunk the result is bit-identical to them. */
+int slimpipe_attn_fwd_chunked(const slimpipe_attn_params* p, const void* q_slice,
+                              const void* const* k_chunks, const void* const* v_chunks,
+                              int32_t n_chunks, int64_t chunk_len, void* out, float* lse,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+int slimpipe_attn_bwd_chunked(const slimpipe_attn_params* p, const void* q_slice,
+                              const void* const* k_chunks, const void* const* v_chunks,
+                              int32_t n_chunks, int64_t chunk_len,
+                              const void* out, const void* d_out, const float* lse,
+                              void* dq, int32_t dq_dtype, int32_t dq_accumulate,
+                              float* const* dk_chunks, float* const* dv_chunks, int32_t dkv_accumulate,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
 const char* slimpipe_attn_strerror(int code);
 
 /* Optional per-kernel timing for benchmarks (not part of the paper's method).  While enabled, every

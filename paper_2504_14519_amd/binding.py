@@ -50,6 +50,11 @@ def _load():
     L.slimpipe_attn_fwd.restype = ctypes.c_int
     L.slimpipe_attn_bwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, ctypes.c_size_t, vp]
     L.slimpipe_attn_bwd.restype = ctypes.c_int
+    pp = ctypes.POINTER(vp)
+    L.slimpipe_attn_fwd_chunked.argtypes = [P, vp, pp, pp, i32, i64, vp, vp, vp, ctypes.c_size_t, vp]
+    L.slimpipe_attn_fwd_chunked.restype = ctypes.c_int
+    L.slimpipe_attn_bwd_chunked.argtypes = [P, vp, pp, pp, i32, i64, vp, vp, vp, vp, i32, i32, pp, pp, i32, vp, ctypes.c_size_t, vp]
+    L.slimpipe_attn_bwd_chunked.restype = ctypes.c_int
     L.slimpipe_attn_merge.argtypes = [i32, ctypes.POINTER(vp), ctypes.POINTER(vp), i32, i32, i32, i32, i32, vp, i32, vp, vp]
     L.slimpipe_attn_merge.restype = ctypes.c_int
     L.slimpipe_attn_finalize_bf16.argtypes = [vp, vp, i64, vp]
@@ -147,6 +152,68 @@ def slimpipe_attn_bwd(q_slice, k_prefix, v_prefix, out, d_out, lse, q_offset, kv
                                  1 if dq_accumulate else 0, dk_acc.data_ptr(), dv_acc.data_ptr(),
                                  1 if dkv_accumulate else 0, workspace.data_ptr(), workspace.numel(), _stream()),
            "slimpipe_attn_bwd")
+    return dq
+
+
+def _chunk_table(chunks):
+    """list of tensors -> ctypes array of device pointers (all chunks share shape and strides)."""
+    c0 = chunks[0]
+    for c in chunks:
+        if c.shape != c0.shape or not _same_strides(c, c0):
+            raise SlimpipeError("chunks must share shape and strides")
+    return (ctypes.c_void_p * len(chunks))(*[c.data_ptr() for c in chunks])
+
+
+class _ChunkedKV:
+    """What make_params needs to know of a chunk list: the shape and strides of the virtual prefix."""
+    def __init__(self, chunks):
+        c0 = chunks[0]
+        self.shape = (c0.shape[0], len(chunks) * c0.shape[1], c0.shape[2], c0.shape[3])
+        self._strides = c0.stride()
+
+    def stride(self, i):
+        return self._strides[i]
+
+
+def slimpipe_attn_fwd_chunked(q_slice, k_chunks, v_chunks, q_offset, kv_begin, kv_end, causal=True, scale=None,
+                              out_dtype=BF16, out=None, lse=None):
+    """As slimpipe_attn_fwd with K/V given as lists of equally shaped chunks [B, chunk_len, Hkv, D]."""
+    import torch
+    B, s, Hq, D = q_slice.shape
+    if out is None:
+        out = torch.empty((B, s, Hq, D), device=q_slice.device, dtype=torch.float32 if out_dtype == F32 else torch.bfloat16)
+    if lse is None:
+        lse = torch.empty((B, Hq, s), device=q_slice.device, dtype=torch.float32)
+    p = make_params(q_slice, _ChunkedKV(k_chunks), out, q_offset, kv_begin, kv_end, causal, scale, out_dtype)
+    _check(lib.slimpipe_attn_fwd_chunked(ctypes.byref(p), q_slice.data_ptr(), _chunk_table(k_chunks), _chunk_table(v_chunks),
+                                         len(k_chunks), k_chunks[0].shape[1], out.data_ptr(), lse.data_ptr(), None, 0, _stream()),
+           "slimpipe_attn_fwd_chunked")
+    return out, lse
+
+
+def slimpipe_attn_bwd_chunked(q_slice, k_chunks, v_chunks, out, d_out, lse, q_offset, kv_begin, kv_end, dk_chunks, dv_chunks,
+                              causal=True, scale=None, dq=None, dq_dtype=BF16, dq_accumulate=False, dkv_accumulate=True,
+                              workspace=None):
+    """As slimpipe_attn_bwd with K/V and the fp32 dK/dV accumulators given as lists of chunks."""
+    import torch
+    if dq is None:
+        dq = torch.empty_like(q_slice, dtype=torch.float32 if dq_dtype == F32 else torch.bfloat16)
+    if not _same_strides(dq, q_slice):
+        raise SlimpipeError("dq must have the strides of q")
+    for c in list(dk_chunks) + list(dv_chunks):
+        if not _same_strides(c, k_chunks[0]):
+            raise SlimpipeError("dk/dv chunks must have the strides of the k chunks")
+    p = make_params(q_slice, _ChunkedKV(k_chunks), out, q_offset, kv_begin, kv_end, causal, scale)
+    p.do_stride_b, p.do_stride_s, p.do_stride_h = d_out.stride(0), d_out.stride(1), d_out.stride(2)
+    need = slimpipe_attn_workspace_bytes(p, True)
+    if workspace is None:
+        workspace = torch.empty(need, device=q_slice.device, dtype=torch.uint8)
+    _check(lib.slimpipe_attn_bwd_chunked(ctypes.byref(p), q_slice.data_ptr(), _chunk_table(k_chunks), _chunk_table(v_chunks),
+                                         len(k_chunks), k_chunks[0].shape[1], out.data_ptr(), d_out.data_ptr(), lse.data_ptr(),
+                                         dq.data_ptr(), dq_dtype, 1 if dq_accumulate else 0, _chunk_table(dk_chunks),
+                                         _chunk_table(dv_chunks), 1 if dkv_accumulate else 0, workspace.data_ptr(),
+                                         workspace.numel(), _stream()),
+           "slimpipe_attn_bwd_chunked")
     return dq
 
 

@@ -36,12 +36,13 @@ int compute_units() {
 // rounds of one tile's query stream each.  Cutting every stream into S chunks makes W*S workgroups of
 // 1/S the length: S is the smallest of 1, 2, 4, 8 that comes within 3% of the best rounds/S, as long
 // as a chunk keeps at least 64 query tiles (the prologue and epilogue of a workgroup cost a few tiles).
-int64_t dkdv_key_tiles(const slimpipe_attn_params* p) {
-  const int64_t nkeys = p->kv_end - p->kv_begin, per = dkdv_keys_per_workgroup();
-  return nkeys > 0 ? (nkeys + per - 1) / per : 0;
+int64_t dkdv_key_tiles(const slimpipe_attn_params* p, int n_chunks) {
+  if (p->kv_end <= p->kv_begin) return 0;
+  const int64_t per = dkdv_keys_per_workgroup();
+  return (p->kv_end - kv_grid_origin(p->kv_begin, n_chunks, (int)per) + per - 1) / per;
 }
-int preferred_split(const slimpipe_attn_params* p) {
-  const int64_t tiles = dkdv_key_tiles(p);
+int preferred_split(const slimpipe_attn_params* p, int n_chunks) {
+  const int64_t tiles = dkdv_key_tiles(p, n_chunks);
   const int64_t w = tiles * p->n_kv_heads * p->batch;
   if (w <= 0) return 1;
   const int64_t stream = ((int64_t)p->s_q + 31) / 32 * (p->n_q_heads / p->n_kv_heads);
@@ -57,11 +58,21 @@ int preferred_split(const slimpipe_attn_params* p) {
     if (cost[i] <= best * 1.03) return 1 << i;
   return 1;
 }
-size_t split_bytes(const slimpipe_attn_params* p, int split) {
+size_t split_bytes(const slimpipe_attn_params* p, int n_chunks, int split) {
   if (split <= 1) return 0;
-  return (size_t)split * 2 * (size_t)p->batch * (size_t)p->n_kv_heads * (size_t)(dkdv_key_tiles(p) * dkdv_keys_per_workgroup()) *
-         (size_t)p->head_dim * sizeof(float);
+  return (size_t)split * 2 * (size_t)p->batch * (size_t)p->n_kv_heads *
+         (size_t)(dkdv_key_tiles(p, n_chunks) * dkdv_keys_per_workgroup()) * (size_t)p->head_dim * sizeof(float);
 }
+
+// A chunk list is legal when it covers kv_capacity rows; with more than one chunk the chunk length is a
+// multiple of the dk/dv key tile (256), so that no key tile of any kernel straddles two chunks.
+int check_chunks(const slimpipe_attn_params* p, int32_t n_chunks, int64_t chunk_len) {
+  if (n_chunks < 1 || n_chunks > kMaxChunks || chunk_len < 1) return SLIMPIPE_EINVAL_SHAPE;
+  if (n_chunks * chunk_len < p->kv_capacity) return SLIMPIPE_EINVAL_RANGE;
+  if (n_chunks > 1 && chunk_len % dkdv_keys_per_workgroup() != 0) return SLIMPIPE_EINVAL_SHAPE;
+  return SLIMPIPE_OK;
+}
+
 
 
 // ---- optional per-kernel event timing -------------------------------------------------------
@@ -146,25 +157,34 @@ int slimpipe_attn_workspace_bytes(const slimpipe_attn_params* p, int is_bwd, siz
   if (!bytes) return SLIMPIPE_EINVAL_NULL;
   int rc = slimpipe_attn_validate(p, is_bwd);
   if (rc != SLIMPIPE_OK) return rc;
-  *bytes = is_bwd ? delta_bytes(p) + split_bytes(p, preferred_split(p)) : 0;
+  if (!is_bwd) { *bytes = 0; return SLIMPIPE_OK; }
+  // the tile grid of a chunked call can start up to 255 keys before kv_begin: room for whichever of the
+  // two variants asks for more
+  const size_t one = split_bytes(p, 1, preferred_split(p, 1)), many = split_bytes(p, 2, preferred_split(p, 2));
+  *bytes = delta_bytes(p) + (one > many ? one : many);
   return SLIMPIPE_OK;
 }
 
-int slimpipe_attn_fwd(const slimpipe_attn_params* p, const void* q_slice, const void* k_prefix,
-                      const void* v_prefix, void* out, float* lse, void* workspace, size_t workspace_bytes,
-                      void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
+static int fwd_impl(const slimpipe_attn_params* p, const void* q_slice, const void* const* k_chunks,
+                    const void* const* v_chunks, int32_t n_chunks, int64_t chunk_len, void* out, float* lse,
+                    void* hip_stream) {
   int rc = slimpipe_attn_validate(p, 0);
   if (rc != SLIMPIPE_OK) return rc;
-  if (!q_slice || !out || !lse) return SLIMPIPE_EINVAL_NULL;
-  if (p->kv_end > 0 && (!k_prefix || !v_prefix)) return SLIMPIPE_EINVAL_NULL;
-  if (!aligned16(q_slice) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(out) ||
-      (reinterpret_cast<uintptr_t>(lse) & 3u))
-    return SLIMPIPE_EINVAL_ALIGN;
+  if (!q_slice || !out || !lse || !k_chunks || !v_chunks) return SLIMPIPE_EINVAL_NULL;
+  rc = check_chunks(p, n_chunks, chunk_len);
+  if (rc != SLIMPIPE_OK) return rc;
+  if (!aligned16(q_slice) || !aligned16(out) || (reinterpret_cast<uintptr_t>(lse) & 3u)) return SLIMPIPE_EINVAL_ALIGN;
   FwdArgs a;
+  memset(&a.kv, 0, sizeof(a.kv));
+  for (int i = 0; i < n_chunks; ++i) {
+    if (p->kv_end > 0 && (!k_chunks[i] || !v_chunks[i])) return SLIMPIPE_EINVAL_NULL;
+    if (!aligned16(k_chunks[i]) || !aligned16(v_chunks[i])) return SLIMPIPE_EINVAL_ALIGN;
+    a.kv.k[i] = static_cast<const __bf16*>(k_chunks[i]);
+    a.kv.v[i] = static_cast<const __bf16*>(v_chunks[i]);
+  }
+  a.kv.len = chunk_len;
+  a.kv.n = n_chunks;
   a.q = static_cast<const __bf16*>(q_slice);
-  a.k = static_cast<const __bf16*>(k_prefix);
-  a.v = static_cast<const __bf16*>(v_prefix);
   a.out = out;
   a.lse = lse;
   a.s_q = p->s_q; a.n_q_heads = p->n_q_heads; a.group = p->n_q_heads / p->n_kv_heads;
@@ -179,37 +199,64 @@ int slimpipe_attn_fwd(const slimpipe_attn_params* p, const void* q_slice, const 
   return e == hipSuccess ? SLIMPIPE_OK : SLIMPIPE_ELAUNCH;
 }
 
-int slimpipe_attn_bwd(const slimpipe_attn_params* p, const void* q_slice, const void* k_prefix,
-                      const void* v_prefix, const void* out, const void* d_out, const float* lse, void* dq,
-                      int32_t dq_dtype, int32_t dq_accumulate, float* dk_acc, float* dv_acc,
-                      int32_t dkv_accumulate, void* workspace, size_t workspace_bytes, void* hip_stream) {
+int slimpipe_attn_fwd(const slimpipe_attn_params* p, const void* q_slice, const void* k_prefix,
+                      const void* v_prefix, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                      void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  if (!p) return SLIMPIPE_EINVAL_NULL;
+  return fwd_impl(p, q_slice, &k_prefix, &v_prefix, 1, p->kv_capacity > 0 ? p->kv_capacity : 1, out, lse, hip_stream);
+}
+
+int slimpipe_attn_fwd_chunked(const slimpipe_attn_params* p, const void* q_slice, const void* const* k_chunks,
+                              const void* const* v_chunks, int32_t n_chunks, int64_t chunk_len, void* out, float* lse,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  (void)workspace; (void)workspace_bytes;
+  return fwd_impl(p, q_slice, k_chunks, v_chunks, n_chunks, chunk_len, out, lse, hip_stream);
+}
+
+static int bwd_impl(const slimpipe_attn_params* p, const void* q_slice, const void* const* k_chunks,
+                    const void* const* v_chunks, int32_t n_chunks, int64_t chunk_len, const void* out,
+                    const void* d_out, const float* lse, void* dq, int32_t dq_dtype, int32_t dq_accumulate,
+                    float* const* dk_chunks, float* const* dv_chunks, int32_t dkv_accumulate, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
   int rc = slimpipe_attn_validate(p, 1);
   if (rc != SLIMPIPE_OK) return rc;
-  if (!q_slice || !out || !d_out || !lse || !dq || !dk_acc || !dv_acc) return SLIMPIPE_EINVAL_NULL;
-  if (p->kv_end > 0 && (!k_prefix || !v_prefix)) return SLIMPIPE_EINVAL_NULL;
+  if (!q_slice || !out || !d_out || !lse || !dq || !k_chunks || !v_chunks || !dk_chunks || !dv_chunks) return SLIMPIPE_EINVAL_NULL;
+  rc = check_chunks(p, n_chunks, chunk_len);
+  if (rc != SLIMPIPE_OK) return rc;
   if (dq_dtype != SLIMPIPE_BF16 && dq_dtype != SLIMPIPE_F32) return SLIMPIPE_EINVAL_SHAPE;
   if (dq_accumulate && dq_dtype != SLIMPIPE_F32) return SLIMPIPE_EINVAL_SHAPE;
-  if (!aligned16(q_slice) || !aligned16(k_prefix) || !aligned16(v_prefix) || !aligned16(out) ||
-      !aligned16(d_out) || !aligned16(dq) || !aligned16(dk_acc) || !aligned16(dv_acc) ||
-      (reinterpret_cast<uintptr_t>(lse) & 3u))
+  if (!aligned16(q_slice) || !aligned16(out) || !aligned16(d_out) || !aligned16(dq) || (reinterpret_cast<uintptr_t>(lse) & 3u))
     return SLIMPIPE_EINVAL_ALIGN;
   if (!workspace || workspace_bytes < delta_bytes(p)) return SLIMPIPE_EWORKSPACE;
   if (!aligned16(workspace)) return SLIMPIPE_EINVAL_ALIGN;
   BwdArgs a;
+  memset(&a.kv, 0, sizeof(a.kv));
+  memset(a.dk_acc, 0, sizeof(a.dk_acc));
+  memset(a.dv_acc, 0, sizeof(a.dv_acc));
+  for (int i = 0; i < n_chunks; ++i) {
+    if (!dk_chunks[i] || !dv_chunks[i]) return SLIMPIPE_EINVAL_NULL;
+    if (p->kv_end > 0 && (!k_chunks[i] || !v_chunks[i])) return SLIMPIPE_EINVAL_NULL;
+    if (!aligned16(k_chunks[i]) || !aligned16(v_chunks[i]) || !aligned16(dk_chunks[i]) || !aligned16(dv_chunks[i])) return SLIMPIPE_EINVAL_ALIGN;
+    a.kv.k[i] = static_cast<const __bf16*>(k_chunks[i]);
+    a.kv.v[i] = static_cast<const __bf16*>(v_chunks[i]);
+    a.dk_acc[i] = dk_chunks[i];
+    a.dv_acc[i] = dv_chunks[i];
+  }
+  a.kv.len = chunk_len;
+  a.kv.n = n_chunks;
   a.q = static_cast<const __bf16*>(q_slice);
-  a.k = static_cast<const __bf16*>(k_prefix);
-  a.v = static_cast<const __bf16*>(v_prefix);
   a.out = static_cast<const __bf16*>(out);
   a.d_out = static_cast<const __bf16*>(d_out);
   a.lse = lse;
   a.delta = static_cast<float*>(workspace);
   a.lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + stat_bytes(p));
-  a.dq = dq; a.dk_acc = dk_acc; a.dv_acc = dv_acc;
-  int split = preferred_split(p);
-  while (split > 1 && delta_bytes(p) + split_bytes(p, split) > workspace_bytes) split /= 2;
+  a.dq = dq;
+  int split = preferred_split(p, n_chunks);
+  while (split > 1 && delta_bytes(p) + split_bytes(p, n_chunks, split) > workspace_bytes) split /= 2;
   a.n_split = split;
   a.part = reinterpret_cast<float*>(static_cast<char*>(workspace) + delta_bytes(p));
-  a.nkeys_pad = dkdv_key_tiles(p) * dkdv_keys_per_workgroup();
+  a.nkeys_pad = dkdv_key_tiles(p, n_chunks) * dkdv_keys_per_workgroup();
   a.s_q = p->s_q; a.n_q_heads = p->n_q_heads; a.n_kv_heads = p->n_kv_heads;
   a.group = p->n_q_heads / p->n_kv_heads; a.causal = p->causal;
   a.dq_f32 = (dq_dtype == SLIMPIPE_F32); a.dq_accumulate = dq_accumulate ? 1 : 0;
@@ -228,6 +275,24 @@ int slimpipe_attn_bwd(const slimpipe_attn_params* p, const void* q_slice, const 
       timed(SLIMPIPE_KERNEL_DKDV_REDUCE, st, [&] { return launch_dkdv_reduce(a, p->batch, p->head_dim, st); }) != hipSuccess)
     return SLIMPIPE_ELAUNCH;
   return SLIMPIPE_OK;
+}
+
+int slimpipe_attn_bwd(const slimpipe_attn_params* p, const void* q_slice, const void* k_prefix,
+                      const void* v_prefix, const void* out, const void* d_out, const float* lse, void* dq,
+                      int32_t dq_dtype, int32_t dq_accumulate, float* dk_acc, float* dv_acc,
+                      int32_t dkv_accumulate, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!p) return SLIMPIPE_EINVAL_NULL;
+  return bwd_impl(p, q_slice, &k_prefix, &v_prefix, 1, p->kv_capacity > 0 ? p->kv_capacity : 1, out, d_out, lse, dq, dq_dtype,
+                  dq_accumulate, &dk_acc, &dv_acc, dkv_accumulate, workspace, workspace_bytes, hip_stream);
+}
+
+int slimpipe_attn_bwd_chunked(const slimpipe_attn_params* p, const void* q_slice, const void* const* k_chunks,
+                              const void* const* v_chunks, int32_t n_chunks, int64_t chunk_len, const void* out,
+                              const void* d_out, const float* lse, void* dq, int32_t dq_dtype, int32_t dq_accumulate,
+                              float* const* dk_chunks, float* const* dv_chunks, int32_t dkv_accumulate, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  return bwd_impl(p, q_slice, k_chunks, v_chunks, n_chunks, chunk_len, out, d_out, lse, dq, dq_dtype, dq_accumulate, dk_chunks,
+                  dv_chunks, dkv_accumulate, workspace, workspace_bytes, hip_stream);
 }
 
 int slimpipe_attn_merge(int32_t n_parts, const void* const* outs, const float* const* lses, int32_t part_dtype,

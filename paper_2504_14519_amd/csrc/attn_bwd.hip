@@ -166,17 +166,18 @@ SP_DEV void dq_matrix_phase(const TrBase<D>& lo_kt, const RpBase<D>& lo_k, const
 // dS^T = p (dP^T - delta) with p = exp2(c S^T - lse2) on visible pairs; `hook(i)`, i = 0..3, is called at
 // four points spread over the phase (asynchronous tile copies ride there).
 template <int D, int BN, class H>
-SP_DEV void dq_vector_phase(DqState<D, BN>& st, float c, bool need_mask, int kmax_rel, int g, H&& hook) {
+SP_DEV void dq_vector_phase(DqState<D, BN>& st, float c, bool need_mask, int kmin_rel, int kmax_rel, int g, H&& hook) {
   constexpr int KB = BN / 32;
   if (need_mask) {
-    const int kmax_lane = kmax_rel - 4 * g;
+    // kmin_rel <= key (kb*32 + 8*(i/4) + 4g + i%4) <= kmax_rel, with the lane's part moved to the bounds: the
+    // key numbers are immediates then (a register per element otherwise, hoisted out of the tile loop)
+    const int kmin_lane = kmin_rel - 4 * g, kmax_lane = kmax_rel - 4 * g;
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        // key (kb*32 + 8*(i/4) + 4g + i%4) <= kmax_rel, with the lane's part on the right: the left side is
-        // an immediate (a register per element otherwise, hoisted out of the tile loop)
-        st.s[kb][i] = (kb * 32 + 8 * (i >> 2) + (i & 3)) <= kmax_lane ? st.s[kb][i] : -INFINITY;     // exp2(-inf) = 0
+        const int key = kb * 32 + 8 * (i >> 2) + (i & 3);
+        st.s[kb][i] = ((key >= kmin_lane) & (key <= kmax_lane)) ? st.s[kb][i] : -INFINITY;     // exp2(-inf) = 0
       }
   }
 #pragma unroll
@@ -228,7 +229,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) st.dq[db][i] = 0.f;
 
-  const int64_t lo = a.kv_begin;
+  const int64_t lo = kv_grid_origin(a.kv_begin, a.kv.n, BN);     // first key of the tile grid
   int64_t hi = a.kv_end;
   if (a.causal) {
     const int last_row = (m0 + BM < a.s_q ? m0 + BM : a.s_q);
@@ -239,8 +240,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
   const float c = a.scale_log2e;
 
   if (nt > 0) {
-    const bf16_t* kbase = a.k + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
-    const bf16_t* vbase = a.v + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
+    const int64_t head_off = (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
     auto key0_of = [&](int t) { return lo + (int64_t)t * BN; };
     TileDma<D, BN, GT> dma;
     constexpr int PASSES = TileDma<D, BN, GT>::PASSES;
@@ -249,15 +249,21 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
     const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2;
     const unsigned smem_lds = lds_addr(smem);
     const int gwave_u = wave_u & (NW / 2 - 1);
+    // Group A copies K tiles, group B V tiles; each walks its operand's chunk list tile by tile.
+    const bool copies_k = !group_b;
+    const bf16_t* const* table = copies_k ? a.kv.k : a.kv.v;
+    KvWalk walk;             // the next tile this group copies
+    walk.seek(table, a.kv, lo, head_off, a.kv_stride_s);
+    const int64_t kv_tile_step = (int64_t)BN * a.kv_stride_s;
     struct CopyJob { const bf16_t* src; unsigned dst; int rows; };
-    // tile t of K (slot t % KSLOTS) or V (slot t % VSLOTS); past the end the last tile is copied again
-    auto make_copy = [&](bool is_k, int t) {
-      const int64_t key0 = key0_of(t < nt ? t : nt - 1);
-      const int64_t avail = a.kv_capacity - key0;
+    // tile t (the one the walk stands on) of K (slot t % KSLOTS) or V (slot t % VSLOTS); the walk moves on
+    // unless t is the last tile: past the end the last tile is copied again
+    auto make_copy = [&](int t) {
       CopyJob j;
-      j.src = (is_k ? kbase : vbase) + key0 * a.kv_stride_s;
-      j.dst = smem_lds + (is_k ? K_BASE + (t % KSLOTS) * TILE_BYTES : V_BASE + (t % VSLOTS) * TILE_BYTES);
-      j.rows = avail > BN ? BN : (int)avail;
+      j.src = walk.ptr;
+      j.dst = smem_lds + (copies_k ? K_BASE + (t % KSLOTS) * TILE_BYTES : V_BASE + (t % VSLOTS) * TILE_BYTES);
+      j.rows = walk.rows(a.kv, BN);
+      if (t + 1 < nt) walk.step(table, a.kv, BN, kv_tile_step, head_off, a.kv_stride_s);
       return j;
     };
     auto copy_pass = [&](const CopyJob& j, int n) { dma.issue(j.dst, j.src, row_bytes, j.rows, gwave_u, n); };
@@ -266,19 +272,22 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
     };
     auto vector_phase = [&](int u, const CopyJob& j) {
       const int64_t key0 = key0_of(u);
-      const bool need_mask = (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
-      // last visible key of this lane's query relative to the tile: worked out in the masked tiles only, from
-      // the thread index (nothing lane-dependent is kept in registers across the loop for it)
+      const bool need_mask = (key0 < a.kv_begin) || (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
+      // first key of the range and last visible key of this lane's query relative to the tile: worked out in
+      // the masked tiles only, from the thread index (nothing lane-dependent is kept in registers across the
+      // loop for it)
       const int t2 = fresh(tid);
-      int kmax_rel = BN;
+      int kmin_rel = 0, kmax_rel = BN;
       if (need_mask) {
+        const int64_t kmin = a.kv_begin - key0;
+        kmin_rel = kmin < 0 ? 0 : (int)kmin;
         const int64_t qpos = a.q_offset + wrow0 + (t2 & 31);
         int64_t kmax = a.kv_end - 1;
         if (a.causal && qpos < kmax) kmax = qpos;
         kmax -= key0;
         kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
       }
-      dq_vector_phase<D, BN>(st, c, need_mask, kmax_rel, (t2 >> 5) & 1, [&](int part) { if (part < PASSES) copy_pass(j, part); });
+      dq_vector_phase<D, BN>(st, c, need_mask, kmin_rel, kmax_rel, (t2 >> 5) & 1, [&](int part) { if (part < PASSES) copy_pass(j, part); });
     };
 
     // prologue: the dO rows of the block (all threads), K(0), K(1) (group A), V(0), V(1) (group B)
@@ -289,8 +298,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
       for (int n = 0; n < TileDma<D, BM, T>::PASSES; ++n)
         dma_do.issue(smem_lds + DO_BASE, dobase, (uint32_t)a.do_stride_s * 2, a.s_q - m0, wave_u, n);
     }
-    if (!group_b) { copy_all(make_copy(true, 0)); copy_all(make_copy(true, 1)); }
-    else { copy_all(make_copy(false, 0)); copy_all(make_copy(false, 1)); }
+    copy_all(make_copy(0));
+    copy_all(make_copy(1));
     wait_async();
     TrBase<D> lo_kt;         // K(u-1), transposed
     RpBase<D> lo_k, lo_v;    // K(u), V(u), row-packed
@@ -313,7 +322,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
     };
     // Both groups run the same code; group B starts one phase (one barrier) later and group A idles
     // one phase at the end.  Group A copies K tiles, group B V tiles.
-    const bool copies_k = !group_b;
 #ifdef SLIMPIPE_TRACE
     long long tq_v = 0, tq_b1 = 0, tq_m = 0, tq_w = 0, tq_b2 = 0, tq_t0 = clock64(), tq_w0 = wall_clock64(), tq_last = clock64();
 #define TQ_MARK(var) { long long _n = clock64(); var += _n - tq_last; tq_last = _n; }
@@ -327,7 +335,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
     phase_end();
     TQ_MARK(tq_b2)
     for (int u = 0; u + 1 < nt; ++u) {
-      vector_phase(u, make_copy(copies_k, u + 2));       // tile u+2 rides along
+      vector_phase(u, make_copy(u + 2));                 // tile u+2 rides along
       TQ_MARK(tq_v)
       phase_end();
       TQ_MARK(tq_b1)
@@ -339,7 +347,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
       phase_end();
       TQ_MARK(tq_b2)
     }
-    vector_phase(nt - 1, make_copy(copies_k, nt + 1));   // (clamped: copies the last tile once more)
+    vector_phase(nt - 1, make_copy(nt + 1));             // (copies the last tile once more)
     phase_end();
     dq_matrix_phase<D, BN, true, false>(lo_kt, lo_k, lo_v, lo_do, st);       // dQ of the last tile
     wait_async();
@@ -563,14 +571,20 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
   // (the quotients come out of vector instructions: read them back so that the compiler knows they are uniform)
   const int ktile = __builtin_amdgcn_readfirstlane((int)(blockIdx.x / (unsigned)a.n_split));
   const int split = (int)blockIdx.x - ktile * a.n_split;
-  const int64_t tile_key0 = a.kv_begin + (int64_t)ktile * BNK;
+  // key tiles sit on the grid of kv_grid_origin (absolute multiples of 256 when K/V are chunked): a tile
+  // lies inside one chunk; keys of the first tile before kv_begin are computed and not stored
+  const int64_t grid0 = kv_grid_origin(a.kv_begin, a.kv.n, BNK);
+  const int64_t tile_key0 = grid0 + (int64_t)ktile * BNK;
+  const int kchunk = a.kv.n > 1 ? __builtin_amdgcn_readfirstlane((int)(tile_key0 / a.kv.len)) : 0;
+  const int64_t chunk_row0 = tile_key0 - (int64_t)kchunk * a.kv.len;      // the tile's first row inside its chunk
+  const int64_t head_off = (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
   const int64_t mykey = tile_key0 + wave_u * 32 + ql;
   const int64_t mykey_c = mykey < a.kv_end ? mykey : a.kv_end - 1;
 
   DkdvState<D> st;
   {
     // K as B operand: column = my key, k-slots = head_dim 16*ks + 8g ..
-    const bf16_t* kp = a.k + (int64_t)b * a.kv_stride_b + mykey_c * a.kv_stride_s + (int64_t)hk * a.kv_stride_h;
+    const bf16_t* kp = a.kv.k[kchunk] + head_off + (chunk_row0 + (mykey_c - tile_key0)) * a.kv_stride_s;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) st.kreg[ks] = *reinterpret_cast<const bf16x8*>(kp + 16 * ks + 8 * g);
   }
@@ -712,7 +726,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     {
       TileDma<D, BNK, T> dma_v;
       dma_v.init(tid);
-      const bf16_t* vbase = a.v + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h + tile_key0 * a.kv_stride_s;
+      const bf16_t* vbase = a.kv.v[kchunk] + head_off + chunk_row0 * a.kv_stride_s;
       const int64_t avail = a.kv_end - tile_key0;
       for (int n = 0; n < TileDma<D, BNK, T>::PASSES; ++n)
         dma_v.issue(smem_lds + L::V_BASE, vbase, (uint32_t)a.kv_stride_s * 2, avail > BNK ? BNK : (int)avail, wave_u, n);
@@ -813,7 +827,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
   // registers across the whole loop, and registers are what this kernel is short of)
   const int tid_out = fresh(tid), ql_out = tid_out & 31, g_out = (tid_out >> 5) & 1;
   const int64_t mykey_out = tile_key0 + wave_u * 32 + ql_out;
-  if (mykey_out < a.kv_end) {
+  if (mykey_out >= a.kv_begin && mykey_out < a.kv_end) {
     // one chunk: straight into the accumulators; several: this chunk's partial sums, added up in a
     // fixed order by the reduce kernel
     float* kdst;
@@ -821,14 +835,14 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     bool accumulate;
     if (a.n_split > 1) {
       const int64_t plane = (int64_t)gridDim.z * gridDim.y * a.nkeys_pad * D;          // one of dk / dv of one chunk
-      const int64_t row = (((int64_t)b * gridDim.y + hk) * a.nkeys_pad + (mykey_out - a.kv_begin)) * D;
+      const int64_t row = (((int64_t)b * gridDim.y + hk) * a.nkeys_pad + (mykey_out - grid0)) * D;
       kdst = a.part + (int64_t)split * 2 * plane + row;
       vdst = kdst + plane;
       accumulate = false;
     } else {
-      const int64_t base = (int64_t)b * a.kv_stride_b + mykey_out * a.kv_stride_s + (int64_t)hk * a.kv_stride_h;
-      kdst = a.dk_acc + base;
-      vdst = a.dv_acc + base;
+      const int64_t base = head_off + (chunk_row0 + (mykey_out - tile_key0)) * a.kv_stride_s;
+      kdst = a.dk_acc[kchunk] + base;
+      vdst = a.dv_acc[kchunk] + base;
       accumulate = a.dkv_accumulate != 0;
     }
 #pragma unroll
@@ -860,16 +874,19 @@ __global__ __launch_bounds__(256) void dkdv_reduce_kernel(const BwdArgs a, int b
   const int64_t bh = gid / dvec / nkeys;
   const int hk = (int)(bh % a.n_kv_heads), b = (int)(bh / a.n_kv_heads);
   const int64_t plane = (int64_t)batch * a.n_kv_heads * a.nkeys_pad * head_dim;
-  const float* src = a.part + (bh * a.nkeys_pad + key) * head_dim + d;
+  const int64_t grid0 = kv_grid_origin(a.kv_begin, a.kv.n, dkdv_keys_per_workgroup());
+  const float* src = a.part + (bh * a.nkeys_pad + (a.kv_begin - grid0) + key) * head_dim + d;
   f32x4 k4 = *reinterpret_cast<const f32x4*>(src);
   f32x4 v4 = *reinterpret_cast<const f32x4*>(src + plane);
   for (int s = 1; s < a.n_split; ++s) {
     k4 += *reinterpret_cast<const f32x4*>(src + (int64_t)s * 2 * plane);
     v4 += *reinterpret_cast<const f32x4*>(src + (int64_t)s * 2 * plane + plane);
   }
-  const int64_t base = (int64_t)b * a.kv_stride_b + (a.kv_begin + key) * a.kv_stride_s + (int64_t)hk * a.kv_stride_h + d;
-  f32x4* kd = reinterpret_cast<f32x4*>(a.dk_acc + base);
-  f32x4* vd = reinterpret_cast<f32x4*>(a.dv_acc + base);
+  const int64_t kabs = a.kv_begin + key;
+  const int chunk = a.kv.n > 1 ? (int)(kabs / a.kv.len) : 0;
+  const int64_t base = (int64_t)b * a.kv_stride_b + (kabs - (int64_t)chunk * a.kv.len) * a.kv_stride_s + (int64_t)hk * a.kv_stride_h + d;
+  f32x4* kd = reinterpret_cast<f32x4*>(a.dk_acc[chunk] + base);
+  f32x4* vd = reinterpret_cast<f32x4*>(a.dv_acc[chunk] + base);
   if (a.dkv_accumulate) { k4 += *kd; v4 += *vd; }
   *kd = k4;
   *vd = v4;
@@ -886,8 +903,8 @@ static hipError_t launch_dkdv_t(const BwdArgs& a, int batch, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int64_t nkeys = a.kv_end - a.kv_begin;
-  if (nkeys <= 0) return hipSuccess;
+  if (a.kv_end <= a.kv_begin) return hipSuccess;
+  const int64_t nkeys = a.kv_end - kv_grid_origin(a.kv_begin, a.kv.n, BNK);
   dim3 grid((unsigned)((nkeys + BNK - 1) / BNK) * (unsigned)a.n_split, a.n_kv_heads, batch), block(NW * 64);
   hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, NW>), grid, block, smem, st, a);
   return hipGetLastError();
@@ -906,6 +923,6 @@ hipError_t launch_dkdv_reduce(const BwdArgs& a, int batch, int head_dim, hipStre
   return hipGetLastError();
 }
 
-int dkdv_keys_per_workgroup() { return 8 * 32; }
+
 
 }  // namespace slimpipe

@@ -34,17 +34,19 @@ struct FwdState {
 // kernel, so the work is split evenly between the two kinds of phase): mask + maximum over the first
 // 32 keys of this half-wave's rows at the tail of the matrix phase, the rest in the vector phase.
 template <int D, int BN>
-SP_DEV float fwd_rowmax_first(FwdState<D, BN>& st, bool need_mask, int kmax_rel, int g) {
+SP_DEV float fwd_rowmax_first(FwdState<D, BN>& st, bool need_mask, int kmin_rel, int kmax_rel, int g) {
   constexpr int KB = BN / 32;
   if (need_mask) {
-    // key (kb*32 + 8*(i/4) + 4g + i%4) <= kmax_rel, with the lane's part on the right: the left side is an
-    // immediate (a register per element otherwise, hoisted out of the tile loop)
-    const int kmax_lane = kmax_rel - 4 * g;
+    // kmin_rel <= key (kb*32 + 8*(i/4) + 4g + i%4) <= kmax_rel, with the lane's part moved to the bounds: the
+    // key numbers are immediates then (a register per element otherwise, hoisted out of the tile loop)
+    const int kmin_lane = kmin_rel - 4 * g, kmax_lane = kmax_rel - 4 * g;
 #pragma unroll
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-      for (int i = 0; i < 16; ++i)
-        st.s[kb][i] = (kb * 32 + 8 * (i >> 2) + (i & 3)) <= kmax_lane ? st.s[kb][i] : -INFINITY;
+      for (int i = 0; i < 16; ++i) {
+        const int key = kb * 32 + 8 * (i >> 2) + (i & 3);
+        st.s[kb][i] = ((key >= kmin_lane) & (key <= kmax_lane)) ? st.s[kb][i] : -INFINITY;
+      }
   }
   float mx = -INFINITY;
 #pragma unroll
@@ -222,7 +224,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
   st.m_run = -INFINITY;
   st.l_run = 0.f;
 
-  const int64_t lo = a.kv_begin;
+  const int64_t lo = kv_grid_origin(a.kv_begin, a.kv.n, BN);     // first key of the tile grid
   int64_t hi = a.kv_end;
   if (a.causal) {
     const int last_row = (m0 + BM < a.s_q ? m0 + BM : a.s_q);
@@ -233,8 +235,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
   const float c = a.scale_log2e;
 
   if (nt > 0) {
-    const bf16_t* kbase = a.k + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
-    const bf16_t* vbase = a.v + (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
+    const int64_t head_off = (int64_t)b * a.kv_stride_b + (int64_t)hk * a.kv_stride_h;
     auto key0_of = [&](int t) { return lo + (int64_t)t * BN; };
     // Per tile t a wave runs the matrix phase MM(t): O^T += V(t-1)^T P(t-1)^T, S(t)^T = K(t) Q^T, row maxima
     // of S(t); and the vector phase VV(t): P(t) = online softmax of S(t).  K(t) is read in MM(t) only, V(t) in
@@ -243,7 +244,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
     // K(t+2) during VV(t) into a ring of three slots, group B copies V(t+1) during its VV(t) into a ring
     // of two, and each group waits for its copies at the end of its next matrix phase.  Copies are
     // branch-free: a tile past the end of the range re-copies the last tile (nobody reads it), rows
-    // past the allocation are clamped.
+    // past the end of the chunk are clamped.  Each group walks its operand's chunk list tile by tile.
     constexpr int GT = T / 2;                            // threads of one group
     const int gtid = tid & (GT - 1);
     TileDma<D, BN, GT> dma;
@@ -253,14 +254,19 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
     const uint32_t row_bytes = (uint32_t)a.kv_stride_s * 2;
     const unsigned smem_lds = lds_addr(smem);
     const int gwave_u = wave_u & (NW / 2 - 1);
+    const bool copies_k = !group_b;
+    const bf16_t* const* table = copies_k ? a.kv.k : a.kv.v;
+    KvWalk walk;             // the next tile this group copies
+    walk.seek(table, a.kv, lo, head_off, a.kv_stride_s);
+    const int64_t kv_tile_step = (int64_t)BN * a.kv_stride_s;
     struct CopyJob { const bf16_t* src; unsigned dst; int rows; };
-    auto make_copy = [&](bool is_k, int t) {
-      const int64_t key0 = key0_of(t < nt ? t : nt - 1);
-      const int64_t avail = a.kv_capacity - key0;
+    // tile t (the one the walk stands on) into its ring slot; the walk moves on unless t is the last tile
+    auto make_copy = [&](int t) {
       CopyJob j;
-      j.src = (is_k ? kbase : vbase) + key0 * a.kv_stride_s;
-      j.dst = smem_lds + (is_k ? K_BASE + (t % KSLOTS) * TILE_BYTES : V_BASE + (t % VSLOTS) * TILE_BYTES);
-      j.rows = avail > BN ? BN : (int)avail;
+      j.src = walk.ptr;
+      j.dst = smem_lds + (copies_k ? K_BASE + (t % KSLOTS) * TILE_BYTES : V_BASE + (t % VSLOTS) * TILE_BYTES);
+      j.rows = walk.rows(a.kv, BN);
+      if (t + 1 < nt) walk.step(table, a.kv, BN, kv_tile_step, head_off, a.kv_stride_s);
       return j;
     };
     auto copy_pass = [&](const CopyJob& j, int n) { dma.issue(j.dst, j.src, row_bytes, j.rows, gwave_u, n); };
@@ -274,24 +280,25 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
     // tail of a matrix phase: mask S(t) and take its row maxima (balances the two kinds of phase)
     auto rowmax_tile = [&](int t) {
       const int64_t key0 = key0_of(t);
-      const bool need_mask = (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
+      const bool need_mask = (key0 < a.kv_begin) || (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
       const int t2 = fresh(tid);
-      int kmax_rel = BN;
-      if (need_mask) {       // last visible key of this lane's query relative to the tile
+      int kmin_rel = 0, kmax_rel = BN;
+      if (need_mask) {       // first key of the range and last visible key of this lane's query, relative to the tile
+        const int64_t kmin = a.kv_begin - key0;
+        kmin_rel = kmin < 0 ? 0 : (int)kmin;
         const int64_t qpos = a.q_offset + wrow0 + (t2 & 31);
         int64_t kmax = a.kv_end - 1;
         if (a.causal && qpos < kmax) kmax = qpos;
         kmax -= key0;
         kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
       }
-      st.mx = fwd_rowmax_first<D, BN>(st, need_mask, kmax_rel, (t2 >> 5) & 1);
+      st.mx = fwd_rowmax_first<D, BN>(st, need_mask, kmin_rel, kmax_rel, (t2 >> 5) & 1);
       asm volatile("" : "+v"(st.mx));      // keep it on this side of the phase barrier
     };
 
     // prologue: K(0), K(1) (group A), V(0) (group B)
-    const bool copies_k = !group_b;
-    if (copies_k) { copy_all(make_copy(true, 0)); copy_all(make_copy(true, 1)); }
-    else copy_all(make_copy(false, 0));
+    if (copies_k) { copy_all(make_copy(0)); copy_all(make_copy(1)); }
+    else copy_all(make_copy(0));
     wait_async();
     RpOffsets<D> lo_k;       // K(t), row-packed (registers are plentiful here: one offset per head_dim block)
     TrOffsets<D> lo_v;       // V(t-1), transposed
@@ -322,7 +329,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
     phase_end();
     TP_MARK(tp_b2)
     for (int t = 0; t + 1 < nt; ++t) {
-      vector_phase(copies_k ? make_copy(true, t + 2) : make_copy(false, t + 1));
+      vector_phase(make_copy(copies_k ? t + 2 : t + 1));
       TP_MARK(tp_v)
       phase_end();
       TP_MARK(tp_b1)
@@ -335,7 +342,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
       phase_end();
       TP_MARK(tp_b2)
     }
-    vector_phase(copies_k ? make_copy(true, nt + 1) : make_copy(false, nt));
+    vector_phase(make_copy(copies_k ? nt + 1 : nt));
     phase_end();
     { FwdMatrixPhase<D, BN, true, false, 2> ph{lo_v, lo_k, st}; ph.run(); }
     wait_async();

@@ -5,10 +5,28 @@
 
 namespace slimpipe {
 
+// The cached keys / values as the paper stores them (Sec. 5): a list of slice-sized chunks rather than
+// one buffer.  Row j of the prefix is row j % len of chunk j / len; inside a chunk rows follow the kv
+// strides.  A contiguous prefix is the list of one chunk (any length).  With more than one chunk `len`
+// is a multiple of 256 and the kernels walk key tiles on an absolute grid, so that no tile straddles two
+// chunks.
+constexpr int kMaxChunks = 64;
+struct KvChunks {
+  const __bf16* k[kMaxChunks];
+  const __bf16* v[kMaxChunks];
+  int64_t len;
+  int32_t n;
+};
+// keys one workgroup of the dk/dv kernel owns
+inline __host__ __device__ constexpr int dkdv_keys_per_workgroup() { return 8 * 32; }
+// first key of the tile grid for tiles of `tile` keys
+inline __host__ __device__ int64_t kv_grid_origin(int64_t kv_begin, int32_t n_chunks, int tile) {
+  return n_chunks > 1 ? kv_begin / tile * tile : kv_begin;
+}
+
 struct FwdArgs {
   const __bf16* q;
-  const __bf16* k;
-  const __bf16* v;
+  KvChunks kv;
   void* out;
   float* lse;
   int32_t s_q, n_q_heads, group, causal, out_f32;
@@ -21,16 +39,15 @@ struct FwdArgs {
 
 struct BwdArgs {
   const __bf16* q;
-  const __bf16* k;
-  const __bf16* v;
+  KvChunks kv;
   const __bf16* out;
   const __bf16* d_out;
   const float* lse;
   float* delta;            // workspace [batch, n_q_heads, s_q]: rowsum(dO * O)
   float* lse2;             // workspace [batch, n_q_heads, s_q]: lse * log2(e), +inf where lse = -inf
   void* dq;
-  float* dk_acc;
-  float* dv_acc;
+  float* dk_acc[kMaxChunks];   // float32 accumulators, chunked like the keys / values
+  float* dv_acc[kMaxChunks];
   float* part;             // workspace [n_split][2][batch][n_kv_heads][nkeys_pad][head_dim]: partial dk, dv (n_split > 1)
   int32_t n_split;         // chunks the query stream of a key tile is cut into (one workgroup each)
   int64_t nkeys_pad;       // key rows per (batch, kv head) plane of `part`
@@ -58,7 +75,6 @@ hipError_t launch_delta(const BwdArgs& a, int batch, int head_dim, hipStream_t s
 hipError_t launch_bwd_dq(const BwdArgs& a, int batch, int head_dim, hipStream_t st);
 hipError_t launch_bwd_dkdv(const BwdArgs& a, int batch, int head_dim, hipStream_t st);
 hipError_t launch_dkdv_reduce(const BwdArgs& a, int batch, int head_dim, hipStream_t st);
-int dkdv_keys_per_workgroup();
 hipError_t launch_merge(const MergeArgs& a, hipStream_t st);
 hipError_t launch_finalize(const float* acc, __bf16* dst, int64_t n, hipStream_t st);
 hipError_t launch_mfma_rate(int random, int iters, int workgroups, float* sink, hipStream_t st);

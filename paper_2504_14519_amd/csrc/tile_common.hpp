@@ -3,6 +3,8 @@
 // patterns (row-packed for contraction over head_dim, transposed for contraction over rows).
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include "kernels.hpp"
 #include <stdint.h>
 
 namespace slimpipe {
@@ -244,6 +246,34 @@ struct TileDma {
     const uint32_t off = (uint32_t)r * row_bytes + (rcv >> 16);
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :: "v"(off), "s"(tile_base), "s"(lds) : "memory", "m0");
+  }
+};
+
+// Walks the key tiles of a chunked K/V prefix in increasing order: where the tile "now" starts.  All
+// members are uniform.  A step is two additions; the chunk's base pointer (a scalar load from the
+// kernel arguments) and the product row * stride are needed only when the walk enters a new chunk.
+struct KvWalk {
+  const bf16_t* ptr;       // first row of the tile (batch and head offset included)
+  int chunk, row;          // current chunk, first row of the tile inside it
+  SP_DEV void seek(const bf16_t* const* table, const KvChunks& kv, int64_t key0, int64_t head_off, int64_t stride_s) {
+    chunk = kv.n > 1 ? __builtin_amdgcn_readfirstlane((int)(key0 / kv.len)) : 0;
+    row = (int)(key0 - (int64_t)chunk * kv.len);
+    ptr = table[chunk] + head_off + (int64_t)row * stride_s;
+  }
+  // to the next tile; tile_step = tile * stride_s
+  SP_DEV void step(const bf16_t* const* table, const KvChunks& kv, int tile, int64_t tile_step, int64_t head_off, int64_t stride_s) {
+    row += tile;
+    ptr += tile_step;
+    if (row >= kv.len && chunk + 1 < kv.n) {
+      row -= (int)kv.len;
+      ++chunk;
+      ptr = table[chunk] + head_off + (int64_t)row * stride_s;
+    }
+  }
+  // rows of the chunk from the tile's first row on, at most `tile`
+  SP_DEV int rows(const KvChunks& kv, int tile) const {
+    const int64_t left = kv.len - row;
+    return left > tile ? tile : (int)left;
   }
 };
 

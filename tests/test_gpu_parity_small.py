@@ -237,3 +237,55 @@ def test_dkdv_split_query_stream(sp):
     # the split only changes the order of fp32 additions
     assert torch.allclose(res["split"][0], res["unsplit"][0], rtol=1e-4, atol=1e-4)
     assert torch.allclose(res["split"][1], res["unsplit"][1], rtol=1e-4, atol=1e-4)
+
+
+@pytest.mark.parametrize("kv_begin,kv_end", [(0, 2048), (300, 1900)])
+def test_chunked_kv(sp, kv_begin, kv_end):
+    """K/V (and the dK/dV accumulators) as a list of slice-sized chunks that are separate allocations:
+    same results as the oracle on the concatenated prefix; with an aligned range bit-identical to the
+    contiguous calls (the tile walk is the same), with an unaligned one within the tolerances."""
+    import torch
+    B, s, Hq, Hkv, D, chunk, nch = 1, 512, 4, 2, 128, 512, 4
+    N, q_off = chunk * nch, 1536
+    scale = 1.0 / math.sqrt(D)
+    qb, kb, vb, dob = normal_bf16((B, s, Hq, D), 10, "q"), normal_bf16((B, N, Hkv, D), 10, "k"), normal_bf16((B, N, Hkv, D), 10, "v"), normal_bf16((B, s, Hq, D), 10, "do")
+    q64, k64, v64, do64 = (bf16_bits_to_f64(x) for x in (qb, kb, vb, dob))
+    q, k, v, do = dev_bf16(qb), dev_bf16(kb), dev_bf16(vb), dev_bf16(dob)
+    # separate allocations in shuffled order, with something else allocated in between
+    order = [2, 0, 3, 1]
+    kc, vc, pad = [None] * nch, [None] * nch, []
+    for i in order:
+        kc[i] = k[:, i * chunk:(i + 1) * chunk].clone()
+        pad.append(torch.empty(4096 + 512 * i, device="cuda:0"))
+        vc[i] = v[:, i * chunk:(i + 1) * chunk].clone()
+    say("chunked fwd [%d, %d)" % (kv_begin, kv_end))
+    o_c, l_c = sp.slimpipe_attn_fwd_chunked(q, kc, vc, q_off, kv_begin, kv_end, True, scale)
+    o_f, l_f = sp.slimpipe_attn_fwd(q, k, v, q_off, kv_begin, kv_end, True, scale)
+    torch.cuda.synchronize()
+    o_ref, l_ref = attn_fwd(q64, k64, v64, q_off, kv_begin, kv_end, True, scale)
+    check_fwd("chunked fwd", o_c, l_c, o_ref, l_ref)
+    dq_ref, dk_ref, dv_ref = attn_bwd(q64, k64, v64, host_f64(o_c), do64, host_f64(l_c), q_off, kv_begin, kv_end, True, scale)
+    dkc = [torch.full((B, chunk, Hkv, D), 1.0, device="cuda:0") for _ in range(nch)]
+    dvc = [torch.full((B, chunk, Hkv, D), -2.0, device="cuda:0") for _ in range(nch)]
+    say("chunked bwd")
+    dq_c = sp.slimpipe_attn_bwd_chunked(q, kc, vc, o_c, do, l_c, q_off, kv_begin, kv_end, dkc, dvc, True, scale, dq_dtype=sp.F32,
+                                        dkv_accumulate=True)
+    dk_f = torch.full((B, N, Hkv, D), 1.0, device="cuda:0")
+    dv_f = torch.full((B, N, Hkv, D), -2.0, device="cuda:0")
+    dq_f = sp.slimpipe_attn_bwd(q, k, v, o_c, do, l_c, q_off, kv_begin, kv_end, dk_f, dv_f, True, scale, dq_dtype=sp.F32,
+                                dkv_accumulate=True)
+    torch.cuda.synchronize()
+    dk_c, dv_c = torch.cat(dkc, dim=1), torch.cat(dvc, dim=1)
+    check_grad("chunked dq", dq_c, dq_ref)
+    check_grad("chunked dk", dk_c[:, kv_begin:kv_end] - 1.0, dk_ref[:, kv_begin:kv_end])
+    check_grad("chunked dv", dv_c[:, kv_begin:kv_end] + 2.0, dv_ref[:, kv_begin:kv_end])
+    # rows outside the range are untouched
+    outside = torch.ones(N, dtype=torch.bool); outside[kv_begin:kv_end] = False
+    assert torch.all(dk_c.cpu()[:, outside] == 1.0) and torch.all(dv_c.cpu()[:, outside] == -2.0)
+    if kv_begin % 256 == 0:
+        assert torch.equal(o_c, o_f) and torch.equal(l_c, l_f) and torch.equal(dq_c, dq_f)
+        assert torch.equal(dk_c, dk_f) and torch.equal(dv_c, dv_f)
+    else:
+        assert torch.allclose(dq_c, dq_f, rtol=1e-3, atol=1e-3) and torch.allclose(dk_c, dk_f, rtol=1e-3, atol=1e-3)
+        assert torch.allclose(dv_c, dv_f, rtol=1e-3, atol=1e-3)
+    del pad
