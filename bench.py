@@ -43,6 +43,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="llama70b_tp8_share")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chunked", action="store_true",
+                    help="K/V and the dK/dV accumulators as one allocation per slice (the paper's chunked cache) instead of one buffer")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % args.gpus,
@@ -94,7 +96,31 @@ def main():
     def qs(j):
         return slice(j * s, (j + 1) * s)
 
-    def step():
+    if args.chunked:
+        # one allocation per slice, as the paper keeps its cache; the contiguous buffers are dropped
+        kc = [k[:, i * s:(i + 1) * s].clone() for i in range(n)]
+        vc = [v[:, i * s:(i + 1) * s].clone() for i in range(n)]
+        dkc = [torch.zeros((1, s, Hkv, D), device=dev, dtype=torch.float32) for _ in range(n)]
+        dvc = [torch.zeros((1, s, Hkv, D), device=dev, dtype=torch.float32) for _ in range(n)]
+        dkoc = [dk_out[:, i * s:(i + 1) * s] for i in range(n)]
+        dvoc = [dv_out[:, i * s:(i + 1) * s] for i in range(n)]
+        del k, v, dk_acc, dv_acc
+
+        def step():
+            for j, i in enumerate(slices):
+                sp.slimpipe_attn_fwd_chunked(q[:, qs(j)], kc, vc, i * s, 0, (i + 1) * s, True, scale, out=outs[j], lse=lses[j])
+            for j in reversed(range(nrun)):
+                i = slices[j]
+                sp.slimpipe_attn_bwd_chunked(q[:, qs(j)], kc, vc, outs[j], do[:, qs(j)], lses[j], i * s, 0, (i + 1) * s, dkc, dvc,
+                                             True, scale, dq=dq[:, qs(j)], dq_dtype=sp.BF16, dkv_accumulate=(j != nrun - 1),
+                                             workspace=ws)
+            for i in range(n):
+                sp.slimpipe_attn_finalize_bf16(dkc[i], dkoc[i])
+                sp.slimpipe_attn_finalize_bf16(dvc[i], dvoc[i])
+    else:
+        step = None
+
+    def step_contiguous():
         for j, i in enumerate(slices):
             sp.slimpipe_attn_fwd(q[:, qs(j)], k, v, i * s, 0, (i + 1) * s, True, scale, out=outs[j], lse=lses[j])
         for j in reversed(range(nrun)):
@@ -104,6 +130,9 @@ def main():
                                  True, scale, dq=dq[:, qs(j)], dq_dtype=sp.BF16, dkv_accumulate=(j != nrun - 1), workspace=ws)
         sp.slimpipe_attn_finalize_bf16(dk_acc, dk_out)
         sp.slimpipe_attn_finalize_bf16(dv_acc, dv_out)
+
+    if step is None:
+        step = step_contiguous
 
     pairs = [visible_pairs(s, i * s, 0, (i + 1) * s) for i in slices]
     pairs_total = sum(pairs)
@@ -154,7 +183,8 @@ def main():
         "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": c["name"], "seq": N, "slices": n, "slice_len": s, "slices_run": [slices[0], slices[-1]],
-                   "q_heads": Hq, "kv_heads": Hkv, "head_dim": D, "flop_convention": "14*D per visible pair per q head"},
+                   "q_heads": Hq, "kv_heads": Hkv, "head_dim": D, "flop_convention": "14*D per visible pair per q head",
+                   "kv_layout": "one chunk per slice" if args.chunked else "contiguous"},
         "pct_of_bf16_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "value_model_flops_12D": round(flops_step_model / (ms_per_step * 1e-3) / 1e12, 2),
         "roofline": roofline,

@@ -240,3 +240,37 @@ def test_redistribution_split_merge(sp):
             say("  split vs unsplit backward %s: rel-L2 %.3e" % (nm, e))
             assert e <= TOL_GRAD
         del q, do, o_u, l_u, ps, o_m, l_m, dk_u, dv_u, dq_u, dk_s, dv_s, dq_s
+
+
+def test_llama70b_chunked_matches_contiguous(sp):
+    """The benchmark's launch shape with the cache as 16 slice-sized allocations: forward and backward
+    of the last slice equal the contiguous calls bit for bit (same tile walk, same order of sums), and
+    the contiguous calls are the ones checked against the oracle above."""
+    import torch
+    cfg_id = 2
+    c = CONFIGS[cfg_id]
+    N, n, Hq, Hkv, D = c["N"], c["n"], c["Hq"], c["Hkv"], c["D"]
+    s = N // n
+    i = n - 1
+    say("config %s chunked: generating inputs" % c["name"])
+    k, v = dev_bf16(normal_bf16((1, N, Hkv, D), cfg_id, "k")), dev_bf16(normal_bf16((1, N, Hkv, D), cfg_id, "v"))
+    q = dev_bf16(normal_bf16((1, s, Hq, D), cfg_id, "q", salt=i + 1))
+    do = dev_bf16(normal_bf16((1, s, Hq, D), cfg_id, "do", salt=100 + i))
+    kc = [k[:, j * s:(j + 1) * s].clone() for j in range(n)]
+    vc = [v[:, j * s:(j + 1) * s].clone() for j in range(n)]
+    say("forward, contiguous and chunked")
+    o_f, l_f = sp.slimpipe_attn_fwd(q, k, v, i * s, 0, N, True, None)
+    o_c, l_c = sp.slimpipe_attn_fwd_chunked(q, kc, vc, i * s, 0, N, True, None)
+    torch.cuda.synchronize()
+    assert torch.equal(o_f, o_c) and torch.equal(l_f, l_c)
+    say("backward, contiguous")
+    dk_f = torch.zeros((1, N, Hkv, D), device="cuda:0")
+    dv_f = torch.zeros_like(dk_f)
+    dq_f = sp.slimpipe_attn_bwd(q, k, v, o_f, do, l_f, i * s, 0, N, dk_f, dv_f, True, None, dkv_accumulate=False)
+    say("backward, chunked")
+    dkc = [torch.zeros((1, s, Hkv, D), device="cuda:0") for _ in range(n)]
+    dvc = [torch.zeros((1, s, Hkv, D), device="cuda:0") for _ in range(n)]
+    dq_c = sp.slimpipe_attn_bwd_chunked(q, kc, vc, o_f, do, l_f, i * s, 0, N, dkc, dvc, True, None, dkv_accumulate=False)
+    torch.cuda.synchronize()
+    assert torch.equal(dq_f, dq_c)
+    assert torch.equal(dk_f, torch.cat(dkc, dim=1)) and torch.equal(dv_f, torch.cat(dvc, dim=1))
