@@ -45,6 +45,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunked", action="store_true",
                     help="K/V and the dK/dV accumulators as one allocation per slice (the paper's chunked cache) instead of one buffer")
+    ap.add_argument("--schedule-sim", default=None, metavar="P,M",
+                    help="also time every slice's forward and backward call and feed the times to the slice-wise 1F1B "
+                         "schedule simulator with P pipeline devices and M microbatches (adds a 'schedule_sim' object)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % args.gpus,
@@ -106,33 +109,46 @@ def main():
         dvoc = [dv_out[:, i * s:(i + 1) * s] for i in range(n)]
         del k, v, dk_acc, dv_acc
 
-        def step():
-            for j, i in enumerate(slices):
-                sp.slimpipe_attn_fwd_chunked(q[:, qs(j)], kc, vc, i * s, 0, (i + 1) * s, True, scale, out=outs[j], lse=lses[j])
-            for j in reversed(range(nrun)):
-                i = slices[j]
-                sp.slimpipe_attn_bwd_chunked(q[:, qs(j)], kc, vc, outs[j], do[:, qs(j)], lses[j], i * s, 0, (i + 1) * s, dkc, dvc,
-                                             True, scale, dq=dq[:, qs(j)], dq_dtype=sp.BF16, dkv_accumulate=(j != nrun - 1),
-                                             workspace=ws)
+        def fwd_call(j):
+            i = slices[j]
+            sp.slimpipe_attn_fwd_chunked(q[:, qs(j)], kc, vc, i * s, 0, (i + 1) * s, True, scale, out=outs[j], lse=lses[j])
+
+        def bwd_call(j):
+            i = slices[j]
+            sp.slimpipe_attn_bwd_chunked(q[:, qs(j)], kc, vc, outs[j], do[:, qs(j)], lses[j], i * s, 0, (i + 1) * s, dkc, dvc,
+                                         True, scale, dq=dq[:, qs(j)], dq_dtype=sp.BF16, dkv_accumulate=(j != nrun - 1),
+                                         workspace=ws)
+
+        def finalize():
             for i in range(n):
                 sp.slimpipe_attn_finalize_bf16(dkc[i], dkoc[i])
                 sp.slimpipe_attn_finalize_bf16(dvc[i], dvoc[i])
     else:
-        step = None
-
-    def step_contiguous():
-        for j, i in enumerate(slices):
+        def fwd_call(j):
+            i = slices[j]
             sp.slimpipe_attn_fwd(q[:, qs(j)], k, v, i * s, 0, (i + 1) * s, True, scale, out=outs[j], lse=lses[j])
-        for j in reversed(range(nrun)):
+
+        def bwd_call(j):
             i = slices[j]
             # the last slice to run backward first overwrites its dK/dV rows; earlier slices add to them
             sp.slimpipe_attn_bwd(q[:, qs(j)], k, v, outs[j], do[:, qs(j)], lses[j], i * s, 0, (i + 1) * s, dk_acc, dv_acc,
                                  True, scale, dq=dq[:, qs(j)], dq_dtype=sp.BF16, dkv_accumulate=(j != nrun - 1), workspace=ws)
-        sp.slimpipe_attn_finalize_bf16(dk_acc, dk_out)
-        sp.slimpipe_attn_finalize_bf16(dv_acc, dv_out)
 
-    if step is None:
-        step = step_contiguous
+        def finalize():
+            sp.slimpipe_attn_finalize_bf16(dk_acc, dk_out)
+            sp.slimpipe_attn_finalize_bf16(dv_acc, dv_out)
+
+    def step(mark=None):
+        """Forward of every slice in sequence order, backward in reverse order, dK/dV to bf16."""
+        for j in range(nrun):
+            fwd_call(j)
+            if mark:
+                mark("F", j)
+        for j in reversed(range(nrun)):
+            bwd_call(j)
+            if mark:
+                mark("B", j)
+        finalize()
 
     pairs = [visible_pairs(s, i * s, 0, (i + 1) * s) for i in slices]
     pairs_total = sum(pairs)
@@ -190,9 +206,42 @@ def main():
         "roofline": roofline,
     }
 
+    if args.schedule_sim:
+        out["schedule_sim"] = schedule_sim(args.schedule_sim, n, nrun, slices, step, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg_id, c, s, scale)
     print(json.dumps(out), flush=True)
+
+
+def schedule_sim(spec, n, nrun, slices, step, torch):
+    """Per-slice attention times of this GPU (events on the stream the calls go to, after each slice's forward
+    call and each slice's backward call, inside one more pass of the step) -> what the paper's schedule makes of
+    them: bubble fraction without the context exchange and with it, accumulated activation (Sec. 4.1.3, 4.2)."""
+    from paper_2504_14519_amd.schedule_sim import simulate, accumulated_fraction
+    p_dev, m_mb = (int(x) for x in spec.split(","))
+    if nrun != n or slices[0] != 0:
+        return {"error": "needs a workload that runs every slice"}
+    marks = []
+
+    def mark(kind, j):
+        e = torch.cuda.Event(enable_timing=True)
+        e.record()
+        marks.append((kind, j, e))
+
+    mark("start", -1)
+    step(mark)
+    torch.cuda.synchronize()
+    t = {"F": [0.0] * n, "B": [0.0] * n}
+    for (_, _, e0), (kind, j, e1) in zip(marks[:-1], marks[1:]):
+        t[kind][j] = e0.elapsed_time(e1)
+    res = {"p": p_dev, "m": m_mb, "n": n, "fwd_ms_by_slice": [round(x, 3) for x in t["F"]],
+           "bwd_ms_by_slice": [round(x, 3) for x in t["B"]],
+           "accumulated_activation_fraction_of_Ma": round(accumulated_fraction(p_dev, n, max(m_mb, 2 * p_dev)), 4),
+           "warmup_cooldown_bound": round((p_dev - 1.0) / (n * m_mb), 5), "bubble_fraction": {}}
+    for mode in (None, "pairwise", "balanced", "ideal"):
+        r = simulate(p_dev, n, m_mb, t["F"], t["B"], exchange=mode)
+        res["bubble_fraction"][mode or "no_exchange"] = round(r["bubble_fraction"], 5)
+    return res
 
 
 def stored_traffic(workload, kernel):

@@ -1,0 +1,126 @@
+"""The slice-wise 1F1B schedule simulator against what the paper fixes: the pass order drawn in
+Fig. slim_schedule, the accumulated activation of Eq. 1 and the bubble fractions, both with the values
+plotted in Fig. memory_dec, and the direction of the imbalance-bubble claims of Sec. 4.2.  CPU only."""
+import json
+import os
+
+import pytest
+
+from paper_2504_14519_amd.schedule_sim import (device_order, accumulated_slices, accumulated_fraction, exchange_groups,
+                                               exchanged_loads, simulate, pass_time)
+
+with open(os.path.join(os.path.dirname(__file__), "golden", "slim_schedule.json")) as f:
+    FIG = json.load(f)
+
+
+def test_pass_order_of_the_figure():
+    p, n = FIG["p"], FIG["n"]
+    for dev in range(1, p + 1):
+        order = device_order(p, n, 5, dev - 1)
+        warm = FIG["forward_passes_before_first_backward"][dev - 1]
+        assert [o[0] for o in order[:warm]] == ["F"] * warm and order[warm][0] == "B"
+        assert order[:warm] == [("F", f // n, f % n) for f in range(warm)]
+        drawn = [(kind, k - 1, i - 1) for kind, k, i in FIG["passes_after_warmup"][str(dev)]]
+        assert order[warm:warm + len(drawn)] == drawn
+
+
+def test_every_pass_once_and_backward_after_forward():
+    for p, n, m in [(1, 1, 1), (2, 2, 1), (4, 8, 3), (8, 8, 2), (4, 12, 5)]:
+        for r in range(p):
+            order = device_order(p, n, m, r)
+            assert sorted(order) == sorted([(kd, k, i) for kd in "FB" for k in range(m) for i in range(n)])
+            at = {o: j for j, o in enumerate(order)}
+            for k in range(m):
+                for i in range(n):
+                    assert at[("F", k, i)] < at[("B", k, i)]
+                    if i + 1 < n:          # last in, first out inside a microbatch
+                        assert at[("B", k, i + 1)] < at[("B", k, i)] and at[("F", k, i)] < at[("F", k, i + 1)]
+
+
+def test_aligned_moments_of_the_figure():
+    p, n = FIG["p"], FIG["n"]
+    groups = exchange_groups(p, n, 3)
+    def group_of(kind, dev, k, i):
+        for key, members in groups.items():
+            if key[0] == kind and (dev - 1, k - 1, i - 1) in members:
+                return key
+    fw = {group_of("F", *x) for x in FIG["aligned_moment"]["forward"]}
+    bw = {group_of("B", *x) for x in FIG["aligned_moment"]["backward"]}
+    assert len(fw) == 1 and len(bw) == 1 and None not in fw | bw
+    # away from the junctures the loads of a full group are a progression of step one, heaviest on device 1
+    members = sorted(groups[("F", 2 * n + p)])
+    assert [i for _, _, i in members] == [p - 1 - r + (2 * n + p - (p - 1)) % n for r in range(p)]
+
+
+@pytest.mark.parametrize("p", [4, 8, 16])
+def test_accumulated_activation_plotted_values(p):
+    for x, percent in FIG["accumulated_percent_of_Ma"][str(p)].items():
+        n = int(x) * p
+        assert accumulated_slices(p, n, 2 * p, 0) == n + 2 * (p - 1)
+        got = 100.0 * accumulated_fraction(p, n)
+        assert abs(got - percent) < 6e-3, (p, n, got, percent)                 # plotted with 3 decimals
+        assert abs(got - 100.0 * (1 + 2.0 * (p - 1) / n) / p) < 1e-9            # Eq. 1
+    # later stages hold less
+    assert [accumulated_slices(p, 2 * p, 2 * p, r) for r in range(p)] == [2 * p + 2 * (p - 1 - r) for r in range(p)]
+
+
+@pytest.mark.parametrize("m", [2, 4, 8])
+def test_bubble_fraction_plotted_values(m):
+    p = 4
+    for x, frac in FIG["bubble_fraction_p4"][str(m)].items():
+        n = max(1, int(float(x) * p))
+        for tf, tb in ((1.0, 2.0), (0.7, 1.9)):
+            r = simulate(p, n, m, [tf] * n, [tb] * n)
+            assert abs(r["bubble_fraction"] - frac) < 1e-9, (m, n, r["bubble_fraction"], frac)
+            assert abs(r["makespan"] - (m * n + p - 1) * (tf + tb)) < 1e-9
+
+
+def test_attention_dominated_bubbles():
+    # pass time proportional to the attended key-value length (Sec. 4.2.1), backward twice the forward
+    for p, n, m in [(4, 8, 4), (4, 16, 4), (8, 32, 4)]:
+        tf = [float(L) for L in range(1, n + 1)]
+        tb = [2.0 * L for L in range(1, n + 1)]
+        plain = simulate(p, n, m, tf, tb)
+        pair = simulate(p, n, m, tf, tb, exchange="pairwise")
+        bal = simulate(p, n, m, tf, tb, exchange="balanced")
+        ideal = simulate(p, n, m, tf, tb, exchange="ideal")
+        # the exchange moves work, it does not create any
+        for r in (pair, bal, ideal):
+            assert abs(sum(r["busy"]) - sum(plain["busy"])) < 1e-6
+        # imbalance bubbles: without the exchange the bubble is far above the warm-up/cool-down bound ...
+        bound = (p - 1.0) / (n * m)
+        assert plain["bubble_fraction"] > 2 * bound
+        # ... the exchange removes most of it, finer balancing more, and perfectly equal loads reach the bound
+        assert pair["bubble_fraction"] < 0.5 * plain["bubble_fraction"]
+        assert ideal["bubble_fraction"] <= min(pair["bubble_fraction"], bal["bubble_fraction"]) + 1e-12
+        assert abs(ideal["bubble_fraction"] - bound) < 1e-9
+        # and never goes below the paper's long-context figure
+        assert ideal["bubble_fraction"] >= (p - 1.0) * p / ((n + 1.0) * n * m)
+
+
+def test_exchange_conserves_blocks_and_dependencies_hold():
+    p, n, m = 4, 8, 3
+    for mode in ("pairwise", "balanced", "ideal"):
+        loads = exchanged_loads(p, n, m, mode)
+        assert abs(sum(loads.values()) - 2 * p * m * n * (n + 1) / 2) < 1e-9
+    r = simulate(p, n, m, [1.0 + 0.3 * L for L in range(n)], [2.0 + 0.8 * L for L in range(n)], exchange="pairwise",
+                 t_other_fwd=0.5, t_other_bwd=1.0, t_send=0.1)
+    end = {(kd, d, k, i): e for d in range(p) for kd, k, i, s, e in r["timeline"][d]}
+    start = {(kd, d, k, i): s for d in range(p) for kd, k, i, s, e in r["timeline"][d]}
+    for d in range(p):
+        t = 0.0
+        for kd, k, i, s, e in r["timeline"][d]:
+            assert s >= t - 1e-12 and e > s          # one pass at a time
+            t = e
+            if kd == "F" and d > 0:
+                assert s >= end[("F", d - 1, k, i)] + 0.1 - 1e-12
+            if kd == "B" and d < p - 1:
+                assert s >= end[("B", d + 1, k, i)] + 0.1 - 1e-12
+            if kd == "B":
+                assert s >= end[("F", d, k, i)]
+    assert r["peak_slices"] == [n + 2 * (p - 1 - d) for d in range(p)]
+
+
+def test_pass_time_interpolates():
+    t = [1.0, 3.0, 7.0]
+    assert pass_time(t, 2) == 3.0 and pass_time(t, 2.0) == 3.0 and abs(pass_time(t, 2.25) - 4.0) < 1e-12
