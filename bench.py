@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunked", action="store_true",
                     help="K/V and the dK/dV accumulators as one allocation per slice (the paper's chunked cache) instead of one buffer")
+    ap.add_argument("--no-fwd-ranges", action="store_true",
+                    help="never cut a forward call into key ranges (for comparison on workloads with short slices)")
     ap.add_argument("--schedule-sim", default=None, metavar="P,M",
                     help="also time every slice's forward and backward call and feed the times to the slice-wise 1F1B "
                          "schedule simulator with P pipeline devices and M microbatches (adds a 'schedule_sim' object)")
@@ -95,6 +97,10 @@ def main():
     ws_bytes = max(sp.slimpipe_attn_workspace_bytes(sp.make_params(q[:, :s], k, outs[0], i * s, 0, (i + 1) * s, True, scale), True)
                    for i in slices)
     ws = torch.empty(ws_bytes, device=dev, dtype=torch.uint8)
+    # forward: room for partial results when a slice's query blocks would not fill the GPU (0 for the 256K workload)
+    fws_bytes = 0 if args.no_fwd_ranges else max(
+        sp.slimpipe_attn_workspace_bytes(sp.make_params(q[:, :s], k, outs[0], i * s, 0, (i + 1) * s, True, scale), False) for i in slices)
+    fws = torch.empty(fws_bytes, device=dev, dtype=torch.uint8) if fws_bytes else None
 
     def qs(j):
         return slice(j * s, (j + 1) * s)
@@ -111,7 +117,7 @@ def main():
 
         def fwd_call(j):
             i = slices[j]
-            sp.slimpipe_attn_fwd_chunked(q[:, qs(j)], kc, vc, i * s, 0, (i + 1) * s, True, scale, out=outs[j], lse=lses[j])
+            sp.slimpipe_attn_fwd_chunked(q[:, qs(j)], kc, vc, i * s, 0, (i + 1) * s, True, scale, out=outs[j], lse=lses[j], workspace=fws)
 
         def bwd_call(j):
             i = slices[j]
@@ -126,7 +132,7 @@ def main():
     else:
         def fwd_call(j):
             i = slices[j]
-            sp.slimpipe_attn_fwd(q[:, qs(j)], k, v, i * s, 0, (i + 1) * s, True, scale, out=outs[j], lse=lses[j])
+            sp.slimpipe_attn_fwd(q[:, qs(j)], k, v, i * s, 0, (i + 1) * s, True, scale, out=outs[j], lse=lses[j], workspace=fws)
 
         def bwd_call(j):
             i = slices[j]
@@ -200,7 +206,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": c["name"], "seq": N, "slices": n, "slice_len": s, "slices_run": [slices[0], slices[-1]],
                    "q_heads": Hq, "kv_heads": Hkv, "head_dim": D, "flop_convention": "14*D per visible pair per q head",
-                   "kv_layout": "one chunk per slice" if args.chunked else "contiguous"},
+                   "kv_layout": "one chunk per slice" if args.chunked else "contiguous",
+                   "fwd_key_ranges_workspace_bytes": fws_bytes},
         "pct_of_bf16_peak": round(100.0 * value / PEAK_BF16_TFLOPS, 2),
         "value_model_flops_12D": round(flops_step_model / (ms_per_step * 1e-3) / 1e12, 2),
         "roofline": roofline,

@@ -75,19 +75,29 @@ typedef struct slimpipe_attn_params {
  * backward needs).  No device access. */
 int slimpipe_attn_validate(const slimpipe_attn_params* p, int is_bwd);
 
-/* Bytes of device workspace the call would like (0 for forward).  Backward needs two floats per
+/* Bytes of device workspace the call would like.  Forward: 0 unless the call is a short slice over a long
+ * cache whose query blocks leave compute units idle; then room for the float32 partial (out, lse) of the 2 to 16
+ * key ranges of equal work the call is cut into (see slimpipe_attn_fwd).  Backward needs two floats per
  * (batch, q head, row): delta = rowsum(d_out * out) and lse in log2 units, each array rounded up to
  * 256 bytes; slimpipe_attn_bwd refuses less.  On top of that it can use room for partial dk/dv sums:
  * when the key tiles of a call do not fill the GPU's compute units evenly, the query rows of each
  * key tile are cut into 2, 4 or 8 chunks that run as workgroups of their own, each writing float32
  * partial sums [chunk][dk, dv][batch][kv head][keys rounded up to 256][head_dim] that a second kernel adds up
  * in chunk order.  The figure returned here includes that room for the split this call would pick;
- * given less, slimpipe_attn_bwd uses the largest split that fits (down to none). */
+ * given less, slimpipe_attn_bwd uses the largest split that fits (down to none).  In the same way the dq
+ * kernel of a short slice over a long cache is cut into 2 to 16 key ranges of equal work, as the forward is,
+ * with float32 partial dq [range][batch, s_q, n_q_heads, head_dim] behind the partial dk/dv that a reduce kernel
+ * adds up in range order; that room is included too and used as far as it is there. */
 int slimpipe_attn_workspace_bytes(const slimpipe_attn_params* p, int is_bwd, size_t* bytes);
 
 /* Forward of one query slice against keys [kv_begin, kv_end) of the cached prefix
  * (Sec. 4.1.2; partial ranges: Sec. 4.2.2).  Writes out (dtype p->out_dtype, strides o_*) and
- * lse [batch, n_q_heads, s_q].  Scores are never stored. */
+ * lse [batch, n_q_heads, s_q].  Scores are never stored.
+ *   workspace : may be NULL.  Given slimpipe_attn_workspace_bytes(p, 0) > 0 bytes, a call whose query blocks
+ *               would not fill the GPU cuts [kv_begin, kv_end) into ranges of equal work (cut points on
+ *               multiples of 256 keys), computes them in one launch into float32 partials in the workspace and
+ *               merges them (the rule of slimpipe_attn_merge) into (out, lse) in the same call; given less
+ *               room it uses as many ranges as fit, down to the undivided computation. */
 int slimpipe_attn_fwd(const slimpipe_attn_params* p,
                       const void* q_slice, const void* k_prefix, const void* v_prefix,
                       void* out, float* lse,
@@ -148,6 +158,22 @@ int slimpipe_attn_bwd_chunked(const slimpipe_attn_params* p, const void* q_slice
                               float* const* dk_chunks, float* const* dv_chunks, int32_t dkv_accumulate,
                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Forward of one query slice over SEVERAL key ranges in one launch (Sec. 4.2.2: the pieces a context exchange
+ * cuts a slice's keys into; also how a short slice over a long cache fills the GPU).  Keys / values as a chunk
+ * list as above (n_chunks = 1: one buffer).
+ *   n_ranges         : 1 .. 16;  kv_begin[r] <= kv_end[r] <= p->kv_capacity (HOST arrays; p->kv_begin / kv_end
+ *                      are not used).  Ranges may be empty, overlap or leave gaps: each is computed on its own.
+ *   part_out, part_lse : device, float32, [n_ranges][batch, s_q, n_q_heads, head_dim] and
+ *                      [n_ranges][batch, n_q_heads, s_q], contiguous: what slimpipe_attn_fwd would return for
+ *                      each range with out_dtype SLIMPIPE_F32.
+ *   out, lse         : both NULL (parts only), or the merged result of all ranges (out: p->out_dtype, strides
+ *                      o_*), written by the merge kernel in the same call. */
+int slimpipe_attn_fwd_ranges(const slimpipe_attn_params* p, const void* q_slice,
+                             const void* const* k_chunks, const void* const* v_chunks,
+                             int32_t n_chunks, int64_t chunk_len,
+                             int32_t n_ranges, const int64_t* kv_begin, const int64_t* kv_end,
+                             float* part_out, float* part_lse, void* out, float* lse, void* hip_stream);
+
 const char* slimpipe_attn_strerror(int code);
 
 /* Optional per-kernel timing for benchmarks (not part of the paper's method).  While enabled, every
@@ -156,7 +182,8 @@ const char* slimpipe_attn_strerror(int code);
  * since the last read and clears the records.  The only state the library keeps; not thread-safe. */
 enum {
   SLIMPIPE_KERNEL_FWD = 0, SLIMPIPE_KERNEL_DELTA = 1, SLIMPIPE_KERNEL_DQ = 2, SLIMPIPE_KERNEL_DKDV = 3,
-  SLIMPIPE_KERNEL_MERGE = 4, SLIMPIPE_KERNEL_FINALIZE = 5, SLIMPIPE_KERNEL_DKDV_REDUCE = 6, SLIMPIPE_KERNEL_KINDS = 7
+  SLIMPIPE_KERNEL_MERGE = 4, SLIMPIPE_KERNEL_FINALIZE = 5, SLIMPIPE_KERNEL_DKDV_REDUCE = 6,
+  SLIMPIPE_KERNEL_DQ_REDUCE = 7, SLIMPIPE_KERNEL_KINDS = 8
 };
 int slimpipe_attn_profile_enable(int enable);
 int slimpipe_attn_profile_read(double total_ms[SLIMPIPE_KERNEL_KINDS], int64_t launches[SLIMPIPE_KERNEL_KINDS]);

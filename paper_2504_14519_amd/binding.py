@@ -55,6 +55,8 @@ def _load():
     L.slimpipe_attn_fwd_chunked.restype = ctypes.c_int
     L.slimpipe_attn_bwd_chunked.argtypes = [P, vp, pp, pp, i32, i64, vp, vp, vp, vp, i32, i32, pp, pp, i32, vp, ctypes.c_size_t, vp]
     L.slimpipe_attn_bwd_chunked.restype = ctypes.c_int
+    L.slimpipe_attn_fwd_ranges.argtypes = [P, vp, pp, pp, i32, i64, i32, ctypes.POINTER(i64), ctypes.POINTER(i64), vp, vp, vp, vp, vp]
+    L.slimpipe_attn_fwd_ranges.restype = ctypes.c_int
     L.slimpipe_attn_merge.argtypes = [i32, ctypes.POINTER(vp), ctypes.POINTER(vp), i32, i32, i32, i32, i32, vp, i32, vp, vp]
     L.slimpipe_attn_merge.restype = ctypes.c_int
     L.slimpipe_attn_finalize_bf16.argtypes = [vp, vp, i64, vp]
@@ -118,9 +120,14 @@ def slimpipe_attn_workspace_bytes(params, is_bwd):
     return n.value
 
 
+def _ws(workspace):
+    return (workspace.data_ptr(), workspace.numel()) if workspace is not None else (None, 0)
+
+
 def slimpipe_attn_fwd(q_slice, k_prefix, v_prefix, q_offset, kv_begin, kv_end, causal=True, scale=None,
-                      out_dtype=BF16, out=None, lse=None):
-    """-> (out, lse).  out [B,s,Hq,D] (bf16 or fp32), lse [B,Hq,s] fp32."""
+                      out_dtype=BF16, out=None, lse=None, workspace=None):
+    """-> (out, lse).  out [B,s,Hq,D] (bf16 or fp32), lse [B,Hq,s] fp32.  workspace: uint8 tensor the library may
+    use to cut a short slice over a long cache into key ranges (slimpipe_attn_workspace_bytes(p, False))."""
     import torch
     B, s, Hq, D = q_slice.shape
     if out is None:
@@ -129,7 +136,7 @@ def slimpipe_attn_fwd(q_slice, k_prefix, v_prefix, q_offset, kv_begin, kv_end, c
         lse = torch.empty((B, Hq, s), device=q_slice.device, dtype=torch.float32)
     p = make_params(q_slice, k_prefix, out, q_offset, kv_begin, kv_end, causal, scale, out_dtype)
     _check(lib.slimpipe_attn_fwd(ctypes.byref(p), q_slice.data_ptr(), k_prefix.data_ptr(), v_prefix.data_ptr(),
-                                 out.data_ptr(), lse.data_ptr(), None, 0, _stream()), "slimpipe_attn_fwd")
+                                 out.data_ptr(), lse.data_ptr(), *_ws(workspace), _stream()), "slimpipe_attn_fwd")
     return out, lse
 
 
@@ -176,7 +183,7 @@ class _ChunkedKV:
 
 
 def slimpipe_attn_fwd_chunked(q_slice, k_chunks, v_chunks, q_offset, kv_begin, kv_end, causal=True, scale=None,
-                              out_dtype=BF16, out=None, lse=None):
+                              out_dtype=BF16, out=None, lse=None, workspace=None):
     """As slimpipe_attn_fwd with K/V given as lists of equally shaped chunks [B, chunk_len, Hkv, D]."""
     import torch
     B, s, Hq, D = q_slice.shape
@@ -186,9 +193,40 @@ def slimpipe_attn_fwd_chunked(q_slice, k_chunks, v_chunks, q_offset, kv_begin, k
         lse = torch.empty((B, Hq, s), device=q_slice.device, dtype=torch.float32)
     p = make_params(q_slice, _ChunkedKV(k_chunks), out, q_offset, kv_begin, kv_end, causal, scale, out_dtype)
     _check(lib.slimpipe_attn_fwd_chunked(ctypes.byref(p), q_slice.data_ptr(), _chunk_table(k_chunks), _chunk_table(v_chunks),
-                                         len(k_chunks), k_chunks[0].shape[1], out.data_ptr(), lse.data_ptr(), None, 0, _stream()),
+                                         len(k_chunks), k_chunks[0].shape[1], out.data_ptr(), lse.data_ptr(), *_ws(workspace),
+                                         _stream()),
            "slimpipe_attn_fwd_chunked")
     return out, lse
+
+
+def slimpipe_attn_fwd_ranges(q_slice, k_chunks, v_chunks, q_offset, ranges, causal=True, scale=None, merged=True,
+                             out_dtype=BF16, out=None, lse=None):
+    """One launch over several key ranges [(kv_begin, kv_end), ...] of one query slice; k_chunks / v_chunks: a list
+    of chunks, or one tensor.  -> (part_out [R,B,s,Hq,D] fp32, part_lse [R,B,Hq,s], out, lse); out and lse are the
+    merged result, or None with merged=False."""
+    import torch
+    if not isinstance(k_chunks, (list, tuple)):
+        k_chunks, v_chunks = [k_chunks], [v_chunks]
+    B, s, Hq, D = q_slice.shape
+    R = len(ranges)
+    part_out = torch.empty((R, B, s, Hq, D), device=q_slice.device, dtype=torch.float32)
+    part_lse = torch.empty((R, B, Hq, s), device=q_slice.device, dtype=torch.float32)
+    if merged:
+        if out is None:
+            out = torch.empty((B, s, Hq, D), device=q_slice.device, dtype=torch.float32 if out_dtype == F32 else torch.bfloat16)
+        if lse is None:
+            lse = torch.empty((B, Hq, s), device=q_slice.device, dtype=torch.float32)
+    else:
+        out = lse = None
+    kv = _ChunkedKV(k_chunks)
+    p = make_params(q_slice, kv, out if merged else part_out[0], q_offset, 0, kv.shape[1], causal, scale, out_dtype)
+    begins = (ctypes.c_int64 * R)(*[int(a) for a, _ in ranges])
+    ends = (ctypes.c_int64 * R)(*[int(b) for _, b in ranges])
+    _check(lib.slimpipe_attn_fwd_ranges(ctypes.byref(p), q_slice.data_ptr(), _chunk_table(k_chunks), _chunk_table(v_chunks),
+                                        len(k_chunks), k_chunks[0].shape[1], R, begins, ends, part_out.data_ptr(), part_lse.data_ptr(),
+                                        out.data_ptr() if merged else None, lse.data_ptr() if merged else None, _stream()),
+           "slimpipe_attn_fwd_ranges")
+    return part_out, part_lse, out, lse
 
 
 def slimpipe_attn_bwd_chunked(q_slice, k_chunks, v_chunks, out, d_out, lse, q_offset, kv_begin, kv_end, dk_chunks, dv_chunks,
@@ -245,7 +283,7 @@ def slimpipe_attn_finalize_bf16(acc, dst=None):
     return dst
 
 
-KERNEL_KINDS = ("fwd", "delta", "dq", "dkdv", "merge", "finalize", "dkdv_reduce")
+KERNEL_KINDS = ("fwd", "delta", "dq", "dkdv", "merge", "finalize", "dkdv_reduce", "dq_reduce")
 
 
 def slimpipe_attn_mfma_rate(random_operands):

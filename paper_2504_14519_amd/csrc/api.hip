@@ -64,6 +64,77 @@ size_t split_bytes(const slimpipe_attn_params* p, int n_chunks, int split) {
          (size_t)(dkdv_key_tiles(p, n_chunks) * dkdv_keys_per_workgroup()) * (size_t)p->head_dim * sizeof(float);
 }
 
+// ---- key ranges of one forward launch --------------------------------------------------------------
+// Visible (query, key) pairs of the call with keys in [p->kv_begin, e).
+double visible_pairs_upto(const slimpipe_attn_params* p, int64_t e) {
+  if (e > p->kv_end) e = p->kv_end;
+  if (e <= p->kv_begin) return 0.0;
+  const int64_t s = p->s_q;
+  if (!p->causal) return (double)s * (double)(e - p->kv_begin);
+  // row i sees keys below q_offset + i + 1: rows from i0 on see all of [kv_begin, e), rows i1 .. i0-1 a part
+  int64_t i0 = e - p->q_offset - 1;
+  i0 = i0 < 0 ? 0 : (i0 > s ? s : i0);
+  int64_t i1 = p->kv_begin - p->q_offset;
+  i1 = i1 < 0 ? 0 : (i1 > i0 ? i0 : i1);
+  const double full = (double)(s - i0) * (double)(e - p->kv_begin);
+  const double cnt = (double)(i0 - i1);
+  const double first = (double)(p->q_offset + i1 + 1 - p->kv_begin), last = (double)(p->q_offset + i0 - p->kv_begin);
+  return full + (cnt > 0 ? 0.5 * cnt * (first + last) : 0.0);
+}
+
+// One forward workgroup owns 256 query rows of one head and walks the whole key range; a short slice over a
+// long cache leaves compute units idle.  Cutting the key range into R ranges of equal work (one launch,
+// partial (out, lse) per range, then the online-softmax merge) makes R times the workgroups: R is the
+// smallest count that comes within 3% of the best rounds/R, as long as a range keeps at least 1024 keys.
+int fwd_preferred_ranges(const slimpipe_attn_params* p) {
+  const int64_t w = (((int64_t)p->s_q + 255) / 256) * p->n_q_heads * p->batch;
+  const int64_t keys = p->kv_end - p->kv_begin;
+  if (w <= 0 || keys <= 0) return 1;
+  const int cus = compute_units();
+  double best = 1e30, cost[kMaxRanges + 1];
+  for (int r = 1; r <= kMaxRanges; ++r) {
+    cost[r] = (r > 1 && keys / r < 1024) ? 1e30 : (double)((w * r + cus - 1) / cus) / r;
+    if (cost[r] < best) best = cost[r];
+  }
+  for (int r = 1; r <= kMaxRanges; ++r)
+    if (cost[r] <= best * 1.03) return r;
+  return 1;
+}
+size_t fwd_part_out_bytes(const slimpipe_attn_params* p) {
+  size_t n = (size_t)p->batch * (size_t)p->s_q * (size_t)p->n_q_heads * (size_t)p->head_dim * sizeof(float);
+  return (n + 255) & ~(size_t)255;
+}
+size_t fwd_parts_bytes(const slimpipe_attn_params* p, int ranges) {
+  return ranges <= 1 ? 0 : (size_t)ranges * (fwd_part_out_bytes(p) + stat_bytes(p));
+}
+// The dq kernel has the forward's launch shape and is cut into key ranges the same way; its partial results are
+// float32 [range][batch, s_q, heads, head_dim].
+size_t dq_parts_bytes(const slimpipe_attn_params* p, int ranges) {
+  return ranges <= 1 ? 0 : (size_t)ranges * fwd_part_out_bytes(p);
+}
+// Cut points of equal work on multiples of 256 keys (no range boundary inside a chunk-grid tile).
+void equal_work_ranges(const slimpipe_attn_params* p, int ranges, int64_t* begin, int64_t* end) {
+  const double total = visible_pairs_upto(p, p->kv_end);
+  int64_t prev = p->kv_begin;
+  for (int r = 0; r < ranges; ++r) {
+    int64_t cut = p->kv_end;
+    if (r + 1 < ranges) {
+      const double want = total * (double)(r + 1) / (double)ranges;
+      int64_t lo = prev / 256, hi = (p->kv_end + 255) / 256;        // smallest multiple of 256 with enough pairs below it
+      while (lo < hi) {
+        const int64_t mid = (lo + hi) / 2;
+        if (visible_pairs_upto(p, mid * 256) >= want) hi = mid; else lo = mid + 1;
+      }
+      cut = lo * 256;
+      if (cut < prev) cut = prev;
+      if (cut > p->kv_end) cut = p->kv_end;
+    }
+    begin[r] = prev;
+    end[r] = cut;
+    prev = cut;
+  }
+}
+
 // A chunk list is legal when it covers kv_capacity rows; with more than one chunk the chunk length is a
 // multiple of the dk/dv key tile (256), so that no key tile of any kernel straddles two chunks.
 int check_chunks(const slimpipe_attn_params* p, int32_t n_chunks, int64_t chunk_len) {
@@ -157,27 +228,46 @@ int slimpipe_attn_workspace_bytes(const slimpipe_attn_params* p, int is_bwd, siz
   if (!bytes) return SLIMPIPE_EINVAL_NULL;
   int rc = slimpipe_attn_validate(p, is_bwd);
   if (rc != SLIMPIPE_OK) return rc;
-  if (!is_bwd) { *bytes = 0; return SLIMPIPE_OK; }
+  if (!is_bwd) { *bytes = fwd_parts_bytes(p, fwd_preferred_ranges(p)); return SLIMPIPE_OK; }
   // the tile grid of a chunked call can start up to 255 keys before kv_begin: room for whichever of the
   // two variants asks for more
   const size_t one = split_bytes(p, 1, preferred_split(p, 1)), many = split_bytes(p, 2, preferred_split(p, 2));
-  *bytes = delta_bytes(p) + (one > many ? one : many);
+  *bytes = delta_bytes(p) + (one > many ? one : many) + dq_parts_bytes(p, fwd_preferred_ranges(p));
   return SLIMPIPE_OK;
 }
 
+// Forward over `n_ranges` key ranges in one launch.  With parts == nullptr there is one range and the result
+// goes straight to (out, lse); otherwise range r writes float32 partials at part_out + r * part_out_elems,
+// part_lse + r * part_lse_elems (contiguous [batch, s_q, heads, head_dim] / [batch, heads, s_q]) and, when
+// `out` is given, the merge kernel folds them into (out, lse).
 static int fwd_impl(const slimpipe_attn_params* p, const void* q_slice, const void* const* k_chunks,
-                    const void* const* v_chunks, int32_t n_chunks, int64_t chunk_len, void* out, float* lse,
-                    void* hip_stream) {
+                    const void* const* v_chunks, int32_t n_chunks, int64_t chunk_len, int32_t n_ranges,
+                    const int64_t* range_begin, const int64_t* range_end, float* part_out, int64_t part_out_elems,
+                    float* part_lse, int64_t part_lse_elems, void* out, float* lse, void* hip_stream) {
   int rc = slimpipe_attn_validate(p, 0);
   if (rc != SLIMPIPE_OK) return rc;
-  if (!q_slice || !out || !lse || !k_chunks || !v_chunks) return SLIMPIPE_EINVAL_NULL;
+  const bool parts = part_out != nullptr;
+  if (!q_slice || !k_chunks || !v_chunks || !range_begin || !range_end) return SLIMPIPE_EINVAL_NULL;
+  if (parts ? !part_lse || ((out == nullptr) != (lse == nullptr)) : (!out || !lse)) return SLIMPIPE_EINVAL_NULL;
+  if (n_ranges < 1 || n_ranges > kMaxRanges || (!parts && n_ranges != 1)) return SLIMPIPE_EINVAL_SHAPE;
+  if ((int64_t)p->batch * n_ranges > 65535) return SLIMPIPE_EINVAL_SHAPE;
   rc = check_chunks(p, n_chunks, chunk_len);
   if (rc != SLIMPIPE_OK) return rc;
-  if (!aligned16(q_slice) || !aligned16(out) || (reinterpret_cast<uintptr_t>(lse) & 3u)) return SLIMPIPE_EINVAL_ALIGN;
+  if (!aligned16(q_slice) || (out && (!aligned16(out) || (reinterpret_cast<uintptr_t>(lse) & 3u)))) return SLIMPIPE_EINVAL_ALIGN;
+  if (parts && (!aligned16(part_out) || (reinterpret_cast<uintptr_t>(part_lse) & 3u) || part_out_elems % 4 != 0)) return SLIMPIPE_EINVAL_ALIGN;
   FwdArgs a;
   memset(&a.kv, 0, sizeof(a.kv));
+  int64_t last_key = 0;
+  for (int r = 0; r < kMaxRanges; ++r) {
+    a.range_begin[r] = a.range_end[r] = 0;
+    if (r >= n_ranges) continue;
+    if (range_begin[r] < 0 || range_begin[r] > range_end[r] || range_end[r] > p->kv_capacity) return SLIMPIPE_EINVAL_RANGE;
+    a.range_begin[r] = range_begin[r];
+    a.range_end[r] = range_end[r];
+    if (range_end[r] > last_key) last_key = range_end[r];
+  }
   for (int i = 0; i < n_chunks; ++i) {
-    if (p->kv_end > 0 && (!k_chunks[i] || !v_chunks[i])) return SLIMPIPE_EINVAL_NULL;
+    if (last_key > 0 && (!k_chunks[i] || !v_chunks[i])) return SLIMPIPE_EINVAL_NULL;
     if (!aligned16(k_chunks[i]) || !aligned16(v_chunks[i])) return SLIMPIPE_EINVAL_ALIGN;
     a.kv.k[i] = static_cast<const __bf16*>(k_chunks[i]);
     a.kv.v[i] = static_cast<const __bf16*>(v_chunks[i]);
@@ -185,33 +275,89 @@ static int fwd_impl(const slimpipe_attn_params* p, const void* q_slice, const vo
   a.kv.len = chunk_len;
   a.kv.n = n_chunks;
   a.q = static_cast<const __bf16*>(q_slice);
-  a.out = out;
-  a.lse = lse;
+  a.n_ranges = n_ranges;
   a.s_q = p->s_q; a.n_q_heads = p->n_q_heads; a.group = p->n_q_heads / p->n_kv_heads;
-  a.causal = p->causal; a.out_f32 = (p->out_dtype == SLIMPIPE_F32);
-  a.q_offset = p->q_offset; a.kv_begin = p->kv_begin; a.kv_end = p->kv_end; a.kv_capacity = p->kv_capacity;
+  a.causal = p->causal;
+  a.q_offset = p->q_offset; a.kv_capacity = p->kv_capacity;
   a.scale_log2e = p->scale * 1.4426950408889634f;
   a.q_stride_b = p->q_stride_b; a.q_stride_s = p->q_stride_s; a.q_stride_h = p->q_stride_h;
   a.kv_stride_b = p->kv_stride_b; a.kv_stride_s = p->kv_stride_s; a.kv_stride_h = p->kv_stride_h;
-  a.o_stride_b = p->o_stride_b; a.o_stride_s = p->o_stride_s; a.o_stride_h = p->o_stride_h;
+  if (parts) {
+    a.out = part_out; a.lse = part_lse; a.out_f32 = 1;
+    a.out_range_stride = part_out_elems; a.lse_range_stride = part_lse_elems;
+    a.o_stride_h = p->head_dim; a.o_stride_s = (int64_t)p->n_q_heads * p->head_dim; a.o_stride_b = a.o_stride_s * p->s_q;
+  } else {
+    a.out = out; a.lse = lse; a.out_f32 = (p->out_dtype == SLIMPIPE_F32);
+    a.out_range_stride = 0; a.lse_range_stride = 0;
+    a.o_stride_b = p->o_stride_b; a.o_stride_s = p->o_stride_s; a.o_stride_h = p->o_stride_h;
+  }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipError_t e = timed(SLIMPIPE_KERNEL_FWD, st, [&] { return launch_fwd(a, p->batch, p->head_dim, st); });
-  return e == hipSuccess ? SLIMPIPE_OK : SLIMPIPE_ELAUNCH;
+  if (e != hipSuccess) return SLIMPIPE_ELAUNCH;
+  if (parts && out) {
+    MergeArgs m;
+    memset(&m, 0, sizeof(m));
+    for (int r = 0; r < n_ranges; ++r) {
+      m.outs[r] = part_out + (int64_t)r * part_out_elems;
+      m.lses[r] = part_lse + (int64_t)r * part_lse_elems;
+    }
+    m.n_parts = n_ranges; m.part_f32 = 1; m.out_f32 = (p->out_dtype == SLIMPIPE_F32);
+    m.head_dim = p->head_dim; m.n_q_heads = p->n_q_heads; m.s_q = p->s_q; m.rows = (int64_t)p->batch * p->s_q;
+    m.out = out; m.lse = lse;
+    m.o_stride_b = p->o_stride_b; m.o_stride_s = p->o_stride_s; m.o_stride_h = p->o_stride_h;
+    e = timed(SLIMPIPE_KERNEL_MERGE, st, [&] { return launch_merge(m, st); });
+    if (e != hipSuccess) return SLIMPIPE_ELAUNCH;
+  }
+  return SLIMPIPE_OK;
+}
+
+// One range, or - when the caller lends a workspace and the launch would leave compute units idle - the
+// range cut into pieces of equal work whose partial results are merged in the same call.
+static int fwd_auto(const slimpipe_attn_params* p, const void* q_slice, const void* const* k_chunks,
+                    const void* const* v_chunks, int32_t n_chunks, int64_t chunk_len, void* out, float* lse,
+                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = slimpipe_attn_validate(p, 0);
+  if (rc != SLIMPIPE_OK) return rc;
+  int ranges = workspace ? fwd_preferred_ranges(p) : 1;
+  while (ranges > 1 && fwd_parts_bytes(p, ranges) > workspace_bytes) --ranges;
+  if (ranges <= 1)
+    return fwd_impl(p, q_slice, k_chunks, v_chunks, n_chunks, chunk_len, 1, &p->kv_begin, &p->kv_end, nullptr, 0, nullptr, 0, out,
+                    lse, hip_stream);
+  if (!aligned16(workspace)) return SLIMPIPE_EINVAL_ALIGN;
+  int64_t begin[kMaxRanges], end[kMaxRanges];
+  equal_work_ranges(p, ranges, begin, end);
+  float* part_out = static_cast<float*>(workspace);
+  float* part_lse = reinterpret_cast<float*>(static_cast<char*>(workspace) + (size_t)ranges * fwd_part_out_bytes(p));
+  return fwd_impl(p, q_slice, k_chunks, v_chunks, n_chunks, chunk_len, ranges, begin, end, part_out,
+                  (int64_t)(fwd_part_out_bytes(p) / sizeof(float)), part_lse, (int64_t)(stat_bytes(p) / sizeof(float)), out, lse,
+                  hip_stream);
 }
 
 int slimpipe_attn_fwd(const slimpipe_attn_params* p, const void* q_slice, const void* k_prefix,
                       const void* v_prefix, void* out, float* lse, void* workspace, size_t workspace_bytes,
                       void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
   if (!p) return SLIMPIPE_EINVAL_NULL;
-  return fwd_impl(p, q_slice, &k_prefix, &v_prefix, 1, p->kv_capacity > 0 ? p->kv_capacity : 1, out, lse, hip_stream);
+  return fwd_auto(p, q_slice, &k_prefix, &v_prefix, 1, p->kv_capacity > 0 ? p->kv_capacity : 1, out, lse, workspace,
+                  workspace_bytes, hip_stream);
 }
 
 int slimpipe_attn_fwd_chunked(const slimpipe_attn_params* p, const void* q_slice, const void* const* k_chunks,
                               const void* const* v_chunks, int32_t n_chunks, int64_t chunk_len, void* out, float* lse,
                               void* workspace, size_t workspace_bytes, void* hip_stream) {
-  (void)workspace; (void)workspace_bytes;
-  return fwd_impl(p, q_slice, k_chunks, v_chunks, n_chunks, chunk_len, out, lse, hip_stream);
+  if (!p) return SLIMPIPE_EINVAL_NULL;
+  return fwd_auto(p, q_slice, k_chunks, v_chunks, n_chunks, chunk_len, out, lse, workspace, workspace_bytes, hip_stream);
+}
+
+int slimpipe_attn_fwd_ranges(const slimpipe_attn_params* p, const void* q_slice, const void* const* k_chunks,
+                             const void* const* v_chunks, int32_t n_chunks, int64_t chunk_len, int32_t n_ranges,
+                             const int64_t* kv_begin, const int64_t* kv_end, float* part_out, float* part_lse, void* out,
+                             float* lse, void* hip_stream) {
+  if (!p) return SLIMPIPE_EINVAL_NULL;
+  if (!part_out || !part_lse) return SLIMPIPE_EINVAL_NULL;
+  const int64_t out_elems = (int64_t)p->batch * p->s_q * p->n_q_heads * p->head_dim;
+  const int64_t lse_elems = (int64_t)p->batch * p->n_q_heads * p->s_q;
+  return fwd_impl(p, q_slice, k_chunks, v_chunks, n_chunks, chunk_len, n_ranges, kv_begin, kv_end, part_out, out_elems, part_lse,
+                  lse_elems, out, lse, hip_stream);
 }
 
 static int bwd_impl(const slimpipe_attn_params* p, const void* q_slice, const void* const* k_chunks,
@@ -251,15 +397,33 @@ static int bwd_impl(const slimpipe_attn_params* p, const void* q_slice, const vo
   a.lse = lse;
   a.delta = static_cast<float*>(workspace);
   a.lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + stat_bytes(p));
-  a.dq = dq;
   int split = preferred_split(p, n_chunks);
   while (split > 1 && delta_bytes(p) + split_bytes(p, n_chunks, split) > workspace_bytes) split /= 2;
   a.n_split = split;
   a.part = reinterpret_cast<float*>(static_cast<char*>(workspace) + delta_bytes(p));
+  // what is left of the workspace takes the partial dq of as many key ranges as fit
+  const size_t used = delta_bytes(p) + split_bytes(p, n_chunks, split);
+  int dq_ranges = fwd_preferred_ranges(p);
+  while (dq_ranges > 1 && used + dq_parts_bytes(p, dq_ranges) > workspace_bytes) --dq_ranges;
+  a.n_dq_ranges = dq_ranges;
+  for (int r = 0; r < kMaxRanges; ++r) a.dq_range_begin[r] = a.dq_range_end[r] = 0;
+  if (dq_ranges > 1) {
+    equal_work_ranges(p, dq_ranges, a.dq_range_begin, a.dq_range_end);
+    a.dq = static_cast<char*>(workspace) + used;
+    a.dq_range_stride = (int64_t)(fwd_part_out_bytes(p) / sizeof(float));
+    a.dq_stride_h = p->head_dim; a.dq_stride_s = (int64_t)p->n_q_heads * p->head_dim; a.dq_stride_b = a.dq_stride_s * p->s_q;
+  } else {
+    a.dq_range_begin[0] = p->kv_begin; a.dq_range_end[0] = p->kv_end;
+    a.dq = dq;
+    a.dq_range_stride = 0;
+    a.dq_stride_b = p->q_stride_b; a.dq_stride_s = p->q_stride_s; a.dq_stride_h = p->q_stride_h;
+  }
+  a.dq_final = dq;
+  a.dq_final_f32 = (dq_dtype == SLIMPIPE_F32); a.dq_final_accumulate = dq_accumulate ? 1 : 0;
   a.nkeys_pad = dkdv_key_tiles(p, n_chunks) * dkdv_keys_per_workgroup();
   a.s_q = p->s_q; a.n_q_heads = p->n_q_heads; a.n_kv_heads = p->n_kv_heads;
   a.group = p->n_q_heads / p->n_kv_heads; a.causal = p->causal;
-  a.dq_f32 = (dq_dtype == SLIMPIPE_F32); a.dq_accumulate = dq_accumulate ? 1 : 0;
+  a.dq_f32 = dq_ranges > 1 ? 1 : a.dq_final_f32; a.dq_accumulate = dq_ranges > 1 ? 0 : a.dq_final_accumulate;
   a.dkv_accumulate = dkv_accumulate ? 1 : 0;
   a.q_offset = p->q_offset; a.kv_begin = p->kv_begin; a.kv_end = p->kv_end; a.kv_capacity = p->kv_capacity;
   a.scale = p->scale; a.scale_log2e = p->scale * 1.4426950408889634f;
@@ -270,6 +434,9 @@ static int bwd_impl(const slimpipe_attn_params* p, const void* q_slice, const vo
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (timed(SLIMPIPE_KERNEL_DELTA, st, [&] { return launch_delta(a, p->batch, p->head_dim, st); }) != hipSuccess) return SLIMPIPE_ELAUNCH;
   if (timed(SLIMPIPE_KERNEL_DQ, st, [&] { return launch_bwd_dq(a, p->batch, p->head_dim, st); }) != hipSuccess) return SLIMPIPE_ELAUNCH;
+  if (dq_ranges > 1 &&
+      timed(SLIMPIPE_KERNEL_DQ_REDUCE, st, [&] { return launch_dq_reduce(a, p->batch, p->head_dim, st); }) != hipSuccess)
+    return SLIMPIPE_ELAUNCH;
   if (timed(SLIMPIPE_KERNEL_DKDV, st, [&] { return launch_bwd_dkdv(a, p->batch, p->head_dim, st); }) != hipSuccess) return SLIMPIPE_ELAUNCH;
   if (split > 1 &&
       timed(SLIMPIPE_KERNEL_DKDV_REDUCE, st, [&] { return launch_dkdv_reduce(a, p->batch, p->head_dim, st); }) != hipSuccess)
@@ -316,6 +483,7 @@ int slimpipe_attn_merge(int32_t n_parts, const void* const* outs, const float* c
   a.n_parts = n_parts; a.part_f32 = (part_dtype == SLIMPIPE_F32); a.out_f32 = (out_dtype == SLIMPIPE_F32);
   a.head_dim = head_dim; a.n_q_heads = n_q_heads; a.s_q = s_q; a.rows = (int64_t)batch * s_q;
   a.out = out; a.lse = lse;
+  a.o_stride_h = head_dim; a.o_stride_s = (int64_t)n_q_heads * head_dim; a.o_stride_b = a.o_stride_s * s_q;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipError_t e = timed(SLIMPIPE_KERNEL_MERGE, st, [&] { return launch_merge(a, st); });
   return e == hipSuccess ? SLIMPIPE_OK : SLIMPIPE_ELAUNCH;

@@ -47,8 +47,9 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const MergeArgs a) {
       }
     }
   }
+  const int64_t ooff = bq * a.o_stride_b + r * a.o_stride_s + (int64_t)h * a.o_stride_h + c * 8;
   if (a.out_f32) {
-    f32x4* dst = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.out) + eoff);
+    f32x4* dst = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(a.out) + ooff);
     dst[0] = f32x4{acc[0], acc[1], acc[2], acc[3]};
     dst[1] = f32x4{acc[4], acc[5], acc[6], acc[7]};
   } else {
@@ -59,7 +60,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const MergeArgs a) {
       o[j] = h2[0];
       o[j + 1] = h2[1];
     }
-    *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16_t*>(a.out) + eoff) = o;
+    *reinterpret_cast<bf16x8*>(reinterpret_cast<bf16_t*>(a.out) + ooff) = o;
   }
   if (c == 0) a.lse[sidx] = lse;
 }

@@ -210,7 +210,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
   const bool group_b = wave_u >= NW / 2;
   const int gtid = tid & (GT - 1);
   const int qblk = (int)gridDim.x - 1 - (int)blockIdx.x;
-  const int h = blockIdx.y, b = blockIdx.z, hk = h / a.group;
+  const int h = blockIdx.y, b = (int)blockIdx.z / a.n_dq_ranges, r = (int)blockIdx.z - b * a.n_dq_ranges, hk = h / a.group;
+  const int64_t kv_begin = a.dq_range_begin[r], kv_end = a.dq_range_end[r];      // this workgroup's key range
   const int m0 = qblk * BM, wrow0 = m0 + wave_u * 32;
   const int myrow = wrow0 + ql;
   const int myrow_c = myrow < a.s_q ? myrow : a.s_q - 1;
@@ -229,8 +230,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) st.dq[db][i] = 0.f;
 
-  const int64_t lo = kv_grid_origin(a.kv_begin, a.kv.n, BN);     // first key of the tile grid
-  int64_t hi = a.kv_end;
+  const int64_t lo = kv_grid_origin(kv_begin, a.kv.n, BN);     // first key of the tile grid
+  int64_t hi = kv_end;
   if (a.causal) {
     const int last_row = (m0 + BM < a.s_q ? m0 + BM : a.s_q);
     const int64_t lim = a.q_offset + last_row;
@@ -272,17 +273,17 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
     };
     auto vector_phase = [&](int u, const CopyJob& j) {
       const int64_t key0 = key0_of(u);
-      const bool need_mask = (key0 < a.kv_begin) || (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
+      const bool need_mask = (key0 < kv_begin) || (key0 + BN > kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
       // first key of the range and last visible key of this lane's query relative to the tile: worked out in
       // the masked tiles only, from the thread index (nothing lane-dependent is kept in registers across the
       // loop for it)
       const int t2 = fresh(tid);
       int kmin_rel = 0, kmax_rel = BN;
       if (need_mask) {
-        const int64_t kmin = a.kv_begin - key0;
+        const int64_t kmin = kv_begin - key0;
         kmin_rel = kmin < 0 ? 0 : (int)kmin;
         const int64_t qpos = a.q_offset + wrow0 + (t2 & 31);
-        int64_t kmax = a.kv_end - 1;
+        int64_t kmax = kv_end - 1;
         if (a.causal && qpos < kmax) kmax = qpos;
         kmax -= key0;
         kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
@@ -364,7 +365,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
 
   const int tid_out = fresh(tid), myrow_out = wrow0 + (tid_out & 31), g_out = (tid_out >> 5) & 1;
   if (myrow_out < a.s_q) {
-    const int64_t base = (int64_t)b * a.q_stride_b + (int64_t)myrow_out * a.q_stride_s + (int64_t)h * a.q_stride_h;
+    const int64_t base = (int64_t)r * a.dq_range_stride + (int64_t)b * a.dq_stride_b + (int64_t)myrow_out * a.dq_stride_s +
+                         (int64_t)h * a.dq_stride_h;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -394,7 +396,7 @@ static hipError_t launch_dq_t(const BwdArgs& a, int batch, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  dim3 grid((a.s_q + BM - 1) / BM, a.n_q_heads, batch), block(NW * 64);
+  dim3 grid((a.s_q + BM - 1) / BM, a.n_q_heads, batch * a.n_dq_ranges), block(NW * 64);
   hipLaunchKernelGGL((attn_bwd_dq_kernel<D, NW, BN>), grid, block, smem, st, a);
   return hipGetLastError();
 }
@@ -892,6 +894,30 @@ __global__ __launch_bounds__(256) void dkdv_reduce_kernel(const BwdArgs a, int b
   *vd = v4;
 }
 
+// dq (+)= the partial dq of the key ranges, range 0 first; four head_dim elements per thread.
+__global__ __launch_bounds__(256) void dq_reduce_kernel(const BwdArgs a, int batch, int head_dim) {
+  const int dvec = head_dim / 4;
+  const int64_t total = (int64_t)batch * a.s_q * a.n_q_heads * dvec;
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (gid >= total) return;
+  const int d = (int)(gid % dvec) * 4;
+  const int64_t rh = gid / dvec;                     // (b * s_q + row) * heads + h
+  const int h = (int)(rh % a.n_q_heads);
+  const int64_t brow = rh / a.n_q_heads;
+  const int64_t b = brow / a.s_q, row = brow % a.s_q;
+  const float* src = static_cast<const float*>(a.dq) + b * a.dq_stride_b + row * a.dq_stride_s + (int64_t)h * a.dq_stride_h + d;
+  f32x4 v4 = *reinterpret_cast<const f32x4*>(src);
+  for (int r = 1; r < a.n_dq_ranges; ++r) v4 += *reinterpret_cast<const f32x4*>(src + (int64_t)r * a.dq_range_stride);
+  const int64_t base = b * a.q_stride_b + row * a.q_stride_s + (int64_t)h * a.q_stride_h + d;
+  if (a.dq_final_f32) {
+    f32x4* dst = reinterpret_cast<f32x4*>(static_cast<float*>(a.dq_final) + base);
+    if (a.dq_final_accumulate) v4 += *dst;
+    *dst = v4;
+  } else {
+    *reinterpret_cast<bf16x4*>(static_cast<bf16_t*>(a.dq_final) + base) = __builtin_convertvector(v4, bf16x4);
+  }
+}
+
 template <int D, int NW>
 static hipError_t launch_dkdv_t(const BwdArgs& a, int batch, hipStream_t st) {
   constexpr int BNK = NW * 32;
@@ -913,6 +939,13 @@ static hipError_t launch_dkdv_t(const BwdArgs& a, int batch, hipStream_t st) {
 hipError_t launch_bwd_dkdv(const BwdArgs& a, int batch, int head_dim, hipStream_t st) {
   if (head_dim == 128) return launch_dkdv_t<128, 8>(a, batch, st);
   return launch_dkdv_t<64, 8>(a, batch, st);
+}
+
+hipError_t launch_dq_reduce(const BwdArgs& a, int batch, int head_dim, hipStream_t st) {
+  if (a.n_dq_ranges <= 1) return hipSuccess;
+  const int64_t total = (int64_t)batch * a.s_q * a.n_q_heads * (head_dim / 4);
+  hipLaunchKernelGGL(dq_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a, batch, head_dim);
+  return hipGetLastError();
 }
 
 hipError_t launch_dkdv_reduce(const BwdArgs& a, int batch, int head_dim, hipStream_t st) {

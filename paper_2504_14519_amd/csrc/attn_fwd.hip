@@ -104,7 +104,7 @@ SP_DEV void fwd_softmax(FwdState<D, BN>& st, float c, H&& hook) {
 
 // out = O / l, lse = (m + log2 l) ln 2; rows that saw no key: out = 0, lse = -inf.
 template <int D, int BN>
-SP_DEV void fwd_epilogue(const FwdArgs& a, FwdState<D, BN>& st, int myrow, int h, int b, int g) {
+SP_DEV void fwd_epilogue(const FwdArgs& a, FwdState<D, BN>& st, int myrow, int h, int b, int r, int g) {
   constexpr int DB = D / 32;
   const float l_tot = xhalf_sum(st.l_run);
   const bool has = l_tot > 0.f;
@@ -112,9 +112,10 @@ SP_DEV void fwd_epilogue(const FwdArgs& a, FwdState<D, BN>& st, int myrow, int h
   if (myrow < a.s_q) {
     if (g == 0) {
       const float lse = has ? (st.m_run + __builtin_log2f(l_tot)) * kLn2 : -INFINITY;
-      a.lse[((int64_t)b * a.n_q_heads + h) * a.s_q + myrow] = lse;
+      a.lse[(int64_t)r * a.lse_range_stride + ((int64_t)b * a.n_q_heads + h) * a.s_q + myrow] = lse;
     }
-    const int64_t obase = (int64_t)b * a.o_stride_b + (int64_t)myrow * a.o_stride_s + (int64_t)h * a.o_stride_h;
+    const int64_t obase = (int64_t)r * a.out_range_stride + (int64_t)b * a.o_stride_b + (int64_t)myrow * a.o_stride_s +
+                          (int64_t)h * a.o_stride_h;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -206,7 +207,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);      // known uniform to the compiler
   const bool group_b = wave_u >= NW / 2;
   const int qblk = (int)gridDim.x - 1 - (int)blockIdx.x;
-  const int h = blockIdx.y, b = blockIdx.z, hk = h / a.group;
+  const int h = blockIdx.y, b = (int)blockIdx.z / a.n_ranges, r = (int)blockIdx.z - b * a.n_ranges, hk = h / a.group;
+  const int64_t kv_begin = a.range_begin[r], kv_end = a.range_end[r];      // this workgroup's key range
   const int m0 = qblk * BM, wrow0 = m0 + wave_u * 32;
   const int myrow = wrow0 + ql;
   const int myrow_c = myrow < a.s_q ? myrow : a.s_q - 1;
@@ -224,8 +226,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
   st.m_run = -INFINITY;
   st.l_run = 0.f;
 
-  const int64_t lo = kv_grid_origin(a.kv_begin, a.kv.n, BN);     // first key of the tile grid
-  int64_t hi = a.kv_end;
+  const int64_t lo = kv_grid_origin(kv_begin, a.kv.n, BN);     // first key of the tile grid
+  int64_t hi = kv_end;
   if (a.causal) {
     const int last_row = (m0 + BM < a.s_q ? m0 + BM : a.s_q);
     const int64_t lim = a.q_offset + last_row;
@@ -280,14 +282,14 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
     // tail of a matrix phase: mask S(t) and take its row maxima (balances the two kinds of phase)
     auto rowmax_tile = [&](int t) {
       const int64_t key0 = key0_of(t);
-      const bool need_mask = (key0 < a.kv_begin) || (key0 + BN > a.kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
+      const bool need_mask = (key0 < kv_begin) || (key0 + BN > kv_end) || (a.causal && key0 + BN - 1 > a.q_offset + wrow0);
       const int t2 = fresh(tid);
       int kmin_rel = 0, kmax_rel = BN;
       if (need_mask) {       // first key of the range and last visible key of this lane's query, relative to the tile
-        const int64_t kmin = a.kv_begin - key0;
+        const int64_t kmin = kv_begin - key0;
         kmin_rel = kmin < 0 ? 0 : (int)kmin;
         const int64_t qpos = a.q_offset + wrow0 + (t2 & 31);
-        int64_t kmax = a.kv_end - 1;
+        int64_t kmax = kv_end - 1;
         if (a.causal && qpos < kmax) kmax = qpos;
         kmax -= key0;
         kmax_rel = kmax < -1 ? -1 : (kmax > BN ? BN : (int)kmax);
@@ -356,7 +358,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
     }
 #endif
   }
-  fwd_epilogue<D, BN>(a, st, myrow, h, b, g);
+  fwd_epilogue<D, BN>(a, st, myrow, h, b, r, g);
 }
 
 template <int D, int NW, int BN>
@@ -370,7 +372,7 @@ static hipError_t launch_fwd_t(const FwdArgs& a, int batch, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  dim3 grid((a.s_q + BM - 1) / BM, a.n_q_heads, batch), block(NW * 64);
+  dim3 grid((a.s_q + BM - 1) / BM, a.n_q_heads, batch * a.n_ranges), block(NW * 64);
   hipLaunchKernelGGL((attn_fwd_kernel<D, NW, BN>), grid, block, smem, st, a);
   return hipGetLastError();
 }

@@ -24,13 +24,20 @@ inline __host__ __device__ int64_t kv_grid_origin(int64_t kv_begin, int32_t n_ch
   return n_chunks > 1 ? kv_begin / tile * tile : kv_begin;
 }
 
+// Key ranges one forward launch covers (paper Sec. 4.2.2: the pieces of a context exchange).  Range r
+// of a launch writes its (out, lse) at out + r * out_range_stride, lse + r * lse_range_stride.
+constexpr int kMaxRanges = 16;
+
 struct FwdArgs {
   const __bf16* q;
   KvChunks kv;
   void* out;
   float* lse;
   int32_t s_q, n_q_heads, group, causal, out_f32;
-  int64_t q_offset, kv_begin, kv_end, kv_capacity;
+  int32_t n_ranges;                                   // >= 1; blockIdx.z = batch index * n_ranges + range
+  int64_t range_begin[kMaxRanges], range_end[kMaxRanges];
+  int64_t out_range_stride, lse_range_stride;         // in elements of the output type / floats
+  int64_t q_offset, kv_capacity;
   float scale_log2e;
   int64_t q_stride_b, q_stride_s, q_stride_h;
   int64_t kv_stride_b, kv_stride_s, kv_stride_h;
@@ -49,6 +56,15 @@ struct BwdArgs {
   float* dk_acc[kMaxChunks];   // float32 accumulators, chunked like the keys / values
   float* dv_acc[kMaxChunks];
   float* part;             // workspace [n_split][2][batch][n_kv_heads][nkeys_pad][head_dim]: partial dk, dv (n_split > 1)
+  // dq kernel: key ranges of one launch (blockIdx.z = batch index * n_dq_ranges + range).  With one range dq is the
+  // caller's buffer; with several it is the float32 workspace [range][batch, s_q, heads, head_dim] that
+  // dq_reduce_kernel adds up into dq_final.
+  int32_t n_dq_ranges;
+  int64_t dq_range_begin[kMaxRanges], dq_range_end[kMaxRanges];
+  int64_t dq_range_stride;                       // elements between the partial dq of two ranges
+  int64_t dq_stride_b, dq_stride_s, dq_stride_h; // of `dq` as the dq kernel writes it
+  void* dq_final;                                // the caller's dq (q strides) when n_dq_ranges > 1
+  int32_t dq_final_f32, dq_final_accumulate;
   int32_t n_split;         // chunks the query stream of a key tile is cut into (one workgroup each)
   int64_t nkeys_pad;       // key rows per (batch, kv head) plane of `part`
   int32_t s_q, n_q_heads, n_kv_heads, group, causal;
@@ -66,8 +82,9 @@ struct MergeArgs {
   const float* lses[16];
   int32_t n_parts, part_f32, out_f32, head_dim, n_q_heads, s_q;
   int64_t rows;            // batch * s_q
-  void* out;
+  void* out;               // strides o_* (parts are contiguous [batch, s_q, heads, head_dim])
   float* lse;
+  int64_t o_stride_b, o_stride_s, o_stride_h;
 };
 
 hipError_t launch_fwd(const FwdArgs& a, int batch, int head_dim, hipStream_t st);
@@ -75,6 +92,7 @@ hipError_t launch_delta(const BwdArgs& a, int batch, int head_dim, hipStream_t s
 hipError_t launch_bwd_dq(const BwdArgs& a, int batch, int head_dim, hipStream_t st);
 hipError_t launch_bwd_dkdv(const BwdArgs& a, int batch, int head_dim, hipStream_t st);
 hipError_t launch_dkdv_reduce(const BwdArgs& a, int batch, int head_dim, hipStream_t st);
+hipError_t launch_dq_reduce(const BwdArgs& a, int batch, int head_dim, hipStream_t st);
 hipError_t launch_merge(const MergeArgs& a, hipStream_t st);
 hipError_t launch_finalize(const float* acc, __bf16* dst, int64_t n, hipStream_t st);
 hipError_t launch_mfma_rate(int random, int iters, int workgroups, float* sink, hipStream_t st);

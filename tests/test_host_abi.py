@@ -97,3 +97,29 @@ def test_equal_flop_cuts():
     for e in range(0, 20):
         brute = sum(1 for r in range(s) for j in range(e) if j <= q_off + r)
         assert visible_pairs_upto(s, q_off, e) == brute
+
+
+def test_forward_workspace_asks_for_key_ranges_only_when_the_launch_is_small(sp):
+    import types
+    D = 128
+    def params(s, Hq, Hkv, q_off, kv_end):
+        q = types.SimpleNamespace(shape=(1, s, Hq, D), stride=lambda i, st=(s * Hq * D, Hq * D, D, 1): st[i])
+        k = types.SimpleNamespace(shape=(1, kv_end, Hkv, D), stride=lambda i, st=(kv_end * Hkv * D, Hkv * D, D, 1): st[i])
+        return sp.make_params(q, k, q, q_off, 0, kv_end, True, None)
+    per_range = lambda s, Hq: s * Hq * D * 4 + Hq * s * 4
+    # the benchmark shape: 64 query blocks x 8 heads = two full rounds on 256 compute units, nothing to gain
+    assert sp.slimpipe_attn_workspace_bytes(params(16384, 8, 1, 15 * 16384, 16 * 16384), False) == 0
+    # 4096-row slices of the redistribution workload: 128 workgroups, two ranges fill the GPU
+    assert sp.slimpipe_attn_workspace_bytes(params(4096, 8, 1, 31 * 4096, 32 * 4096), False) == 2 * per_range(4096, 8)
+    # ... but never ranges shorter than 1024 keys
+    assert sp.slimpipe_attn_workspace_bytes(params(256, 8, 1, 1024, 1280), False) == 0
+    assert sp.slimpipe_attn_workspace_bytes(params(256, 1, 1, 8192 - 256, 8192), False) == 8 * per_range(256, 1)
+    # more ranges than 16 are refused, as are ranges outside the cache
+    p = params(256, 8, 1, 1024, 1280)
+    b, e = (ctypes.c_int64 * 17)(*([0] * 17)), (ctypes.c_int64 * 17)(*([64] * 17))
+    one = (ctypes.c_void_p * 1)(64)
+    args = lambda n: (ctypes.byref(p), 64, one, one, 1, 1280, n, b, e, 64, 64, None, None, None)
+    assert sp.lib.slimpipe_attn_fwd_ranges(*args(17)) == -2
+    assert sp.lib.slimpipe_attn_fwd_ranges(*args(0)) == -2
+    e[3] = 1281
+    assert sp.lib.slimpipe_attn_fwd_ranges(*args(4)) == -3
