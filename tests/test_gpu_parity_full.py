@@ -274,3 +274,48 @@ def test_llama70b_chunked_matches_contiguous(sp):
     torch.cuda.synchronize()
     assert torch.equal(dq_f, dq_c)
     assert torch.equal(dk_f, torch.cat(dkc, dim=1)) and torch.equal(dv_f, torch.cat(dvc, dim=1))
+
+
+def test_redistribution_key_ranges_in_one_launch(sp):
+    """The 4096-row slices of the 131072-token workload leave half the compute units idle, so the library
+    cuts the forward and the dq kernel into key ranges when it has the workspace (the launch shape bench.py
+    times for this workload): forward and backward against the oracle on sampled rows, the one-launch
+    multi-range forward against the one-range calls."""
+    import torch
+    from paper_2504_14519_amd.planner import equal_flop_cuts
+    cfg_id = 3
+    c = CONFIGS[cfg_id]
+    N, n, Hq, Hkv, D = c["N"], c["n"], c["Hq"], c["Hkv"], c["D"]
+    s = N // n
+    scale = 1.0 / math.sqrt(D)
+    kb, vb = normal_bf16((1, N, Hkv, D), cfg_id, "k"), normal_bf16((1, N, Hkv, D), cfg_id, "v")
+    k, v = dev_bf16(kb), dev_bf16(vb)
+    k64, v64 = bf16_bits_to_f64(kb), bf16_bits_to_f64(vb)
+    for i in (5, 31):
+        qb = normal_bf16((1, s, Hq, D), cfg_id, "q", salt=i + 1)
+        q, q64 = dev_bf16(qb), bf16_bits_to_f64(qb)
+        kv_end = (i + 1) * s
+        kk, vv = k[:, :kv_end], v[:, :kv_end]
+        out = torch.empty((1, s, Hq, D), device="cuda:0", dtype=torch.bfloat16)
+        need = sp.slimpipe_attn_workspace_bytes(sp.make_params(q, kk, out, i * s, 0, kv_end, True, scale), False)
+        assert need > 0
+        ws = torch.empty(need, device="cuda:0", dtype=torch.uint8)
+        say("redistribution slice %d: forward cut into key ranges (workspace %d bytes)" % (i, need))
+        o_r, l_r = sp.slimpipe_attn_fwd(q, kk, vv, i * s, 0, kv_end, True, scale, out=out, workspace=ws)
+        torch.cuda.synchronize()
+        rows = sample_rows(s, 3, seed=7100 + i)
+        o_ref, l_ref = oracle_rows_fwd(q64, k64[:, :kv_end], v64[:, :kv_end], rows, i * s, 0, kv_end, scale)
+        check_fwd_rows("  ranges vs oracle", o_r, l_r, rows, o_ref, l_ref)
+        # backward with the library's own workspace request: dq in key ranges, dk/dv with a split query stream
+        do_rows = normal_bf16((len(rows), Hq, D), cfg_id, "do", salt=i + 1)
+        sparse_bwd_check(sp, "  slice %d" % i, q, k, v, do_rows, rows, q64, k64, v64, i * s, kv_end, scale, o_r, l_r)
+        # several ranges in one launch == the same ranges one call each, bit for bit
+        cuts = equal_flop_cuts(s, i * s, 3)
+        ranges = list(zip(cuts[:-1], cuts[1:]))
+        po, pl, om, lm = sp.slimpipe_attn_fwd_ranges(q, kk, vv, i * s, ranges, True, scale)
+        for r, (a, b) in enumerate(ranges):
+            o1, l1 = sp.slimpipe_attn_fwd(q, kk, vv, i * s, a, b, True, scale, out_dtype=sp.F32)
+            torch.cuda.synchronize()
+            assert torch.equal(o1, po[r]) and torch.equal(l1, pl[r])
+        check_fwd_rows("  three ranges merged vs oracle", om, lm, rows, o_ref, l_ref)
+        del q, out, ws, o_r, l_r, po, pl, om, lm
