@@ -389,13 +389,8 @@ template <int D, int NW, int BN>
 static hipError_t launch_dq_t(const BwdArgs& a, int batch, hipStream_t st) {
   constexpr int BM = NW * 32;
   const size_t smem = (size_t)6 * BN * D * 2 + (size_t)BM * D * 2;   // 4 K slots + 2 V slots + dO rows
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dq_kernel<D, NW, BN>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsOptIn opt_in;
+  if (hipError_t e = opt_in.ensure(reinterpret_cast<const void*>(&attn_bwd_dq_kernel<D, NW, BN>), smem); e != hipSuccess) return e;
   dim3 grid((a.s_q + BM - 1) / BM, a.n_q_heads, batch * a.n_dq_ranges), block(NW * 64);
   hipLaunchKernelGGL((attn_bwd_dq_kernel<D, NW, BN>), grid, block, smem, st, a);
   return hipGetLastError();
@@ -922,13 +917,8 @@ template <int D, int NW>
 static hipError_t launch_dkdv_t(const BwdArgs& a, int batch, hipStream_t st) {
   constexpr int BNK = NW * 32;
   const size_t smem = DkdvLds<D, NW>::TOTAL;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dkdv_kernel<D, NW>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsOptIn opt_in;
+  if (hipError_t e = opt_in.ensure(reinterpret_cast<const void*>(&attn_bwd_dkdv_kernel<D, NW>), smem); e != hipSuccess) return e;
   if (a.kv_end <= a.kv_begin) return hipSuccess;
   const int64_t nkeys = a.kv_end - kv_grid_origin(a.kv_begin, a.kv.n, BNK);
   dim3 grid((unsigned)((nkeys + BNK - 1) / BNK) * (unsigned)a.n_split, a.n_kv_heads, batch), block(NW * 64);

@@ -365,13 +365,8 @@ template <int D, int NW, int BN>
 static hipError_t launch_fwd_t(const FwdArgs& a, int batch, hipStream_t st) {
   constexpr int BM = NW * 32;
   const size_t smem = (size_t)5 * BN * D * 2;       // K ring of three, V ring of two
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_kernel<D, NW, BN>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static LdsOptIn opt_in;
+  if (hipError_t e = opt_in.ensure(reinterpret_cast<const void*>(&attn_fwd_kernel<D, NW, BN>), smem); e != hipSuccess) return e;
   dim3 grid((a.s_q + BM - 1) / BM, a.n_q_heads, batch * a.n_ranges), block(NW * 64);
   hipLaunchKernelGGL((attn_fwd_kernel<D, NW, BN>), grid, block, smem, st, a);
   return hipGetLastError();

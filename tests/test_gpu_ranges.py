@@ -87,6 +87,14 @@ def test_short_slice_over_long_cache_is_cut_into_ranges():
     assert torch.equal(res[3][0], o0) and torch.equal(res[3][1], l0)
     # the cut only reorders fp32 additions
     assert max_abs(host_f64(res[0][0]), host_f64(o0)) <= 2 ** -7 and max_abs(host_f64(res[0][1]), host_f64(l0)) <= 1e-5
+    # a strided output (heads padded to 160 elements, rows interleaved with something else): same values
+    big = torch.zeros((B, s, 2, Hq, 160), device="cuda:0", dtype=torch.bfloat16)
+    view = big[:, :, 1, :, 16:16 + D]
+    ws = torch.empty(need, device="cuda:0", dtype=torch.uint8)
+    o_s, l_s = sp.slimpipe_attn_fwd(q, k, v, q_off, kv_begin, kv_end, True, scale, out=view, workspace=ws)
+    torch.cuda.synchronize()
+    assert o_s.data_ptr() == view.data_ptr() and torch.equal(view, res[0][0]) and torch.equal(l_s, res[0][1])
+    assert float(big[:, :, 0].abs().max()) == 0.0 and float(big[..., :16].abs().max()) == 0.0 and float(big[..., 16 + D:].abs().max()) == 0.0
     # chunked cache, same call
     kc, vc = [k[:, i:i + 1024].clone() for i in range(0, N, 1024)], [v[:, i:i + 1024].clone() for i in range(0, N, 1024)]
     ws = torch.empty(need, device="cuda:0", dtype=torch.uint8)
