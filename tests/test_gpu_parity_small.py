@@ -289,3 +289,29 @@ def test_chunked_kv(sp, kv_begin, kv_end):
         assert torch.allclose(dq_c, dq_f, rtol=1e-3, atol=1e-3) and torch.allclose(dk_c, dk_f, rtol=1e-3, atol=1e-3)
         assert torch.allclose(dv_c, dv_f, rtol=1e-3, atol=1e-3)
     del pad
+
+
+@pytest.mark.parametrize("s,Nkv,q_off,Hq,Hkv,D", [(1, 1, 0, 1, 1, 128), (1, 300, 299, 2, 1, 64), (5, 3, 0, 3, 3, 128), (33, 65, 32, 2, 2, 64)])
+def test_smallest_shapes(sp, s, Nkv, q_off, Hq, Hkv, D):
+    """One query row, one key, fewer rows than a wave owns: every tile is a ragged tail."""
+    import torch
+    B = 1
+    scale = 1.0 / math.sqrt(D)
+    qb, kb, vb, dob = normal_bf16((B, s, Hq, D), 15, "q", salt=s), normal_bf16((B, Nkv, Hkv, D), 15, "k", salt=s), normal_bf16((B, Nkv, Hkv, D), 15, "v", salt=s), normal_bf16((B, s, Hq, D), 15, "do", salt=s)
+    q64, k64, v64, do64 = (bf16_bits_to_f64(x) for x in (qb, kb, vb, dob))
+    q, k, v, do = dev_bf16(qb), dev_bf16(kb), dev_bf16(vb), dev_bf16(dob)
+    name = "smallest s=%d Nkv=%d q_off=%d" % (s, Nkv, q_off)
+    say(name)
+    o, l = sp.slimpipe_attn_fwd(q, k, v, q_off, 0, Nkv, True, scale, out_dtype=sp.F32)
+    torch.cuda.synchronize()
+    o_ref, l_ref = attn_fwd(q64, k64, v64, q_off, 0, Nkv, True, scale)
+    check_fwd(name, o, l, o_ref, l_ref, bf16_out=False)
+    ob = o.to(torch.bfloat16)
+    dk_acc = torch.zeros((B, Nkv, Hkv, D), device="cuda:0")
+    dv_acc = torch.zeros_like(dk_acc)
+    dq = sp.slimpipe_attn_bwd(q, k, v, ob, do, l, q_off, 0, Nkv, dk_acc, dv_acc, True, scale, dq_dtype=sp.F32, dkv_accumulate=False)
+    torch.cuda.synchronize()
+    dq_r, dk_r, dv_r = attn_bwd(q64, k64, v64, host_f64(ob), do64, host_f64(l), q_off, 0, Nkv, True, scale)
+    check_grad(name + " dq", dq, dq_r)
+    check_grad(name + " dk", dk_acc, dk_r)
+    check_grad(name + " dv", dv_acc, dv_r)
