@@ -421,6 +421,8 @@ struct DkdvState {
   f32x16 dk[DB], dv[DB];
   f32x16 s, dp;
   bf16x8 pb[2], dsb[2];      // 16 query rows each
+  f32x4 lse2v[4];            // lse2 of this lane's 16 rows of the tile in `s`: fetched by the matrix phase (the LDS
+                             // latency passes while the score MFMAs run), used first thing by the vector phase
 };
 
 // LDS layout (bytes): Q ring, dO ring, V rows of the workgroup, statistics ring
@@ -445,11 +447,16 @@ struct DkdvMatrixPhase {
   const RpBase<D>& lo_q;       // Q(u), row-packed; dO(u) sits DO_BASE further
   const RpBase<D>& lo_v;       // this wave's 32 rows of V
   DkdvState<D>& st;
+  const float* stat;           // LDS: lse2 of the rows of tile u, this lane's half (rows 8 i4 + 4 g .. + 3 at [8 i4 .. + 3])
   bf16x8 abuf[NBUF];
   bf16x8 vb[2];
 
   template <int M>
   SP_DEV void reads() {
+    if constexpr (WITH_SCORES && M == N_AC + LOOK + 2) {
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) st.lse2v[i4] = *reinterpret_cast<const f32x4*>(stat + 8 * i4);
+    }
     if constexpr (M < N_AC) {
       constexpr int h = M / (2 * DB), db = (M % (2 * DB)) / 2;
       abuf[M % NBUF] = lds_tr<D>(lo_qt, db, ((M & 1) ? 0 : L::DO_BASE) + h * HALF);
@@ -518,16 +525,15 @@ SP_DEV void dkdv_vector_phase(DkdvState<D>& st, const float* stat, float c, bool
     }
   }
   // Stage by stage over all 16 elements, so that neighbouring instructions do not depend on each other.
-  // The row statistics are read in two batches that share registers (this phase is the register peak
-  // of the kernel): lse2 up front, delta once lse2 is used up, its latency behind the exponentials.  The
-  // copy instructions in the hooks are compiler barriers for memory operations: an LDS read written
-  // after one is not moved above it.
+  // lse2 is in registers already (the matrix phase fetched it: this phase is the longer of the two, and an LDS
+  // read at its start would wait for about 280 cycles behind the reads of the group that is in its matrix
+  // phase); delta is read once lse2 is used up, into the same registers (this phase is the register peak of the
+  // kernel), its latency behind the exponentials.  The copy instructions in the hooks are compiler barriers for
+  // memory operations: an LDS read written after one is not moved above it.
   f32x4 st4[4];
-#pragma unroll
-  for (int i4 = 0; i4 < 4; ++i4) st4[i4] = *reinterpret_cast<const f32x4*>(stat + 8 * i4 + 4 * g);
   hook(0);
 #pragma unroll
-  for (int i = 0; i < 16; ++i) st.s[i] = __builtin_fmaf(st.s[i], c, -st4[i >> 2][i & 3]);
+  for (int i = 0; i < 16; ++i) st.s[i] = __builtin_fmaf(st.s[i], c, -st.lse2v[i >> 2][i & 3]);
   asm volatile("" : "+v"(st.s));          // lse2 is dead from here on
   hook(1);
 #pragma unroll
@@ -750,6 +756,10 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
       lo_qt.add(slot == 0 ? -(SLOTS - 1) * TILE_BYTES : TILE_BYTES);      // Q(u-1) sits in slot - 1
       slot = (slot == SLOTS - 1) ? 0 : slot + 1;
     };
+    // this lane's half of the lse2 of the tile in ring slot `sl`
+    auto stat_of = [&](int sl) {
+      return reinterpret_cast<const float*>(smem + L::STAT_BASE + sl * L::STAT_BYTES) + 4 * ((fresh(tid) >> 5) & 1);
+    };
     // vector phase of tile u (ring slot vslot, first row row0), with the copies of job j riding along
     auto vector_phase = [&](int u, int vslot, int row0, const CopyJob& j) {
       const bool need_mask = seq_lo + u < total_m;
@@ -774,7 +784,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     // Both groups run the same code; group B starts one phase (one barrier) later and group A idles
     // one phase at the end.
     if (group_b) phase_end();
-    { DkdvMatrixPhase<D, NW, false, true, 2> ph{lo_qt, lo_q, lo_v, st}; ph.run(); }     // scores of tile 0
+    { DkdvMatrixPhase<D, NW, false, true, 2> ph{lo_qt, lo_q, lo_v, st, stat_of(0)}; ph.run(); }     // scores of tile 0
     advance();
     wait_async();
     phase_end();
@@ -797,7 +807,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
       TR_MARK(tr_b1)
       // (V never moves: without this the eight offsets of its head_dim blocks are kept in registers across the loop)
       asm volatile("" : "+v"(lo_v.off0));
-      { DkdvMatrixPhase<D, NW, true, true, 2> ph{lo_qt, lo_q, lo_v, st}; ph.run(); }    // sums of tile u, scores of tile u+1
+      { DkdvMatrixPhase<D, NW, true, true, 2> ph{lo_qt, lo_q, lo_v, st, stat_of(vslot)}; ph.run(); }    // sums of tile u, scores of tile u+1
       advance();
       TR_MARK(tr_m)
       wait_async();                                      // the copies of the vector phase before have landed
@@ -807,7 +817,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     }
     vector_phase(cnt - 1, vslot, row0_cur, make_copy(cc, cslot));   // (copies the last tile once more)
     phase_end();
-    { DkdvMatrixPhase<D, NW, true, false, 2> ph{lo_qt, lo_q, lo_v, st}; ph.run(); }     // sums of the last tile
+    { DkdvMatrixPhase<D, NW, true, false, 2> ph{lo_qt, lo_q, lo_v, st, nullptr}; ph.run(); }     // sums of the last tile
     wait_async();
     phase_end();
     if (!group_b) phase_end();
