@@ -23,7 +23,8 @@
 namespace slimpipe {
 
 // ------------------------------------------------------------------------------------ delta
-// delta[b,h,r] = sum_d dO[b,r,h,d] * O[b,r,h,d] and lse2 = lse * log2(e) (+inf for rows that saw no
+// delta[b,h,r] = -sum_d dO[b,r,h,d] * O[b,r,h,d] (NEGATED: the dk/dv kernel starts the accumulator of dP
+// from it, so that the matrix pipe delivers dP - delta) and lse2 = lse * log2(e) (+inf for rows that saw no
 // key, which makes every p of the row exp2(-inf) = 0).  One 16-byte chunk per lane, D/8 lanes per row.
 template <int D>
 __global__ __launch_bounds__(256) void attn_delta_kernel(const BwdArgs a, int batch) {
@@ -50,7 +51,7 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const BwdArgs a, int ba
   for (int w = NC / 2; w >= 1; w >>= 1) acc += __shfl_xor(acc, w, 64);
   if (rh < total && c == 0) {
     const int64_t sidx = ((int64_t)b * a.n_q_heads + h) * a.s_q + r;
-    a.delta[sidx] = acc;
+    a.delta[sidx] = -acc;
     const float l = a.lse[sidx];
     a.lse2[sidx] = (l == -INFINITY) ? INFINITY : l * kLog2e;
   }
@@ -223,7 +224,7 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
     for (int ks = 0; ks < KS; ++ks) st.qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks + 8 * g);
     const int64_t stat = ((int64_t)b * a.n_q_heads + h) * a.s_q + myrow_c;
     st.lse2 = a.lse2[stat];          // +inf for an empty row -> p = 0
-    st.delta = a.delta[stat];
+    st.delta = -a.delta[stat];       // (stored negated)
   }
 #pragma unroll
   for (int db = 0; db < DB; ++db)
@@ -447,7 +448,8 @@ struct DkdvMatrixPhase {
   const RpBase<D>& lo_q;       // Q(u), row-packed; dO(u) sits DO_BASE further
   const RpBase<D>& lo_v;       // this wave's 32 rows of V
   DkdvState<D>& st;
-  const float* stat;           // LDS: lse2 of the rows of tile u, this lane's half (rows 8 i4 + 4 g .. + 3 at [8 i4 .. + 3])
+  const float* stat;           // LDS: lse2 of the rows of tile u, this lane's half (rows 8 i4 + 4 g .. + 3 at [8 i4 .. + 3]);
+                               // -delta of the same rows 32 floats further
   bf16x8 abuf[NBUF];
   bf16x8 vb[2];
 
@@ -456,6 +458,16 @@ struct DkdvMatrixPhase {
     if constexpr (WITH_SCORES && M == N_AC + LOOK + 2) {
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) st.lse2v[i4] = *reinterpret_cast<const f32x4*>(stat + 8 * i4);
+    }
+    // the accumulator of dP(u) starts from -delta of its rows (dP of the tile before was packed into dsb by the
+    // vector phase and is dead): the matrix pipe delivers dP - delta
+    if constexpr (WITH_SCORES && M == (N_AC > 0 ? 2 : 0)) {
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const f32x4 nd = *reinterpret_cast<const f32x4*>(stat + 32 + 8 * i4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) st.dp[4 * i4 + e] = nd[e];
+      }
     }
     if constexpr (M < N_AC) {
       constexpr int h = M / (2 * DB), db = (M % (2 * DB)) / 2;
@@ -480,7 +492,7 @@ struct DkdvMatrixPhase {
       constexpr int j = M - N_AC, ks = j / 2;
       const f32x16 zero = {0};
       if constexpr ((j & 1) == 0) st.s = mfma32(abuf[M % NBUF], st.kreg[ks], ks == 0 ? zero : st.s);
-      else st.dp = mfma32(abuf[M % NBUF], vb[ks & 1], ks == 0 ? zero : st.dp);
+      else st.dp = mfma32(abuf[M % NBUF], vb[ks & 1], st.dp);
     }
   }
   template <int M>
@@ -508,7 +520,7 @@ struct DkdvMatrixPhase {
   }
 };
 
-// P = exp2(c S - lse2) on visible pairs, dS = P (dP - delta); element i of a lane is query row
+// P = exp2(c S - lse2) on visible pairs, dS = P (dP - delta), where `dp` arrives as dP - delta; element i of a lane is query row
 // 8*(i/4) + 4g + i%4 of the tile, the lane's column is its key.  `hook(i)`, i = 0..3, is called at four
 // points spread over the phase (asynchronous tile copies ride there).
 template <int D, class H>
@@ -525,26 +537,18 @@ SP_DEV void dkdv_vector_phase(DkdvState<D>& st, const float* stat, float c, bool
     }
   }
   // Stage by stage over all 16 elements, so that neighbouring instructions do not depend on each other.
-  // lse2 is in registers already (the matrix phase fetched it: this phase is the longer of the two, and an LDS
-  // read at its start would wait for about 280 cycles behind the reads of the group that is in its matrix
-  // phase); delta is read once lse2 is used up, into the same registers (this phase is the register peak of the
-  // kernel), its latency behind the exponentials.  The copy instructions in the hooks are compiler barriers for
-  // memory operations: an LDS read written after one is not moved above it.
-  f32x4 st4[4];
+  // No LDS read here: lse2 is in registers (the matrix phase fetched it) and delta is in dP already.  This
+  // phase is the longer of the two, and an LDS read in it waits for about 280 cycles behind the reads of the
+  // group that is in its matrix phase.
   hook(0);
 #pragma unroll
   for (int i = 0; i < 16; ++i) st.s[i] = __builtin_fmaf(st.s[i], c, -st.lse2v[i >> 2][i & 3]);
-  asm volatile("" : "+v"(st.s));          // lse2 is dead from here on
   hook(1);
 #pragma unroll
-  for (int i4 = 0; i4 < 4; ++i4) st4[i4] = *reinterpret_cast<const f32x4*>(stat + 32 + 8 * i4 + 4 * g);
-#pragma unroll
   for (int i = 0; i < 16; ++i) st.s[i] = exp2_fast(st.s[i]);
-#pragma unroll
-  for (int i = 0; i < 16; ++i) st.dp[i] -= st4[i >> 2][i & 3];
   hook(2);
 #pragma unroll
-  for (int i = 0; i < 16; ++i) st.dp[i] *= st.s[i];
+  for (int i = 0; i < 16; ++i) st.dp[i] *= st.s[i];       // dp holds dP - delta
   hook(3);
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
