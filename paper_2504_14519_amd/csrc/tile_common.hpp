@@ -243,7 +243,8 @@ struct TileDma {
     const uint32_t rcv = (uint32_t)fresh((int)rc);
     int r = (int)(rcv & 0xffffu) + RPP * n;
     r = r < rows_avail ? r : rows_avail - 1;
-    const uint32_t off = (uint32_t)r * row_bytes + (rcv >> 16);
+    // (24-bit multiply, full rate: r < 2^16 and a row is shorter than 2^23 bytes, checked by the host)
+    const uint32_t off = __umul24((uint32_t)r, row_bytes) + (rcv >> 16);
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :: "v"(off), "s"(tile_base), "s"(lds) : "memory", "m0");
   }
