@@ -78,7 +78,7 @@ int slimpipe_attn_validate(const slimpipe_attn_params* p, int is_bwd);
 /* Bytes of device workspace the call would like.  Forward: 0 unless the call is a short slice over a long
  * cache whose query blocks leave compute units idle; then room for the float32 partial (out, lse) of the 2 to 16
  * key ranges of equal work the call is cut into (see slimpipe_attn_fwd).  Backward needs two floats per
- * (batch, q head, row): delta = rowsum(d_out * out) and lse in log2 units, each array rounded up to
+ * (batch, q head, row): delta = rowsum(d_out * out) (kept negated) and lse in log2 units, each array rounded up to
  * 256 bytes; slimpipe_attn_bwd refuses less.  On top of that it can use room for partial dk/dv sums:
  * when the key tiles of a call do not fill the GPU's compute units evenly, the query rows of each
  * key tile are cut into 2, 4 or 8 chunks that run as workgroups of their own, each writing float32

@@ -50,7 +50,7 @@ struct BwdArgs {
   const __bf16* out;
   const __bf16* d_out;
   const float* lse;
-  float* delta;            // workspace [batch, n_q_heads, s_q]: rowsum(dO * O)
+  float* delta;            // workspace [batch, n_q_heads, s_q]: -rowsum(dO * O) (negated: initial accumulator of dP in dk/dv)
   float* lse2;             // workspace [batch, n_q_heads, s_q]: lse * log2(e), +inf where lse = -inf
   void* dq;
   float* dk_acc[kMaxChunks];   // float32 accumulators, chunked like the keys / values
