@@ -84,7 +84,9 @@ struct DqState {
   f32x16 dq[DB];
   f32x16 s[KB], dp[KB];
   bf16x8 ds[KB][2];
-  float lse2, delta;
+  float lse2;
+  f32x16 ndelta;      // -delta of the lane's query in all 16 registers: the initial accumulator of every dP tile,
+                      // so that the matrix pipe delivers dP - delta (the vector unit is the scarcer resource)
 };
 
 // One matrix phase as an explicit software pipeline.  The MFMAs are numbered m = 0 .. N-1 (first the
@@ -129,7 +131,7 @@ struct DqMatrixPhase {
       constexpr int j = M - N_DQ, ks = j / (2 * KB), r = j % (2 * KB), kb = r / 2;
       const f32x16 zero = {0};
       if constexpr ((r & 1) == 0) st.s[kb] = mfma32(abuf[M % NBUF], st.qreg[ks], ks == 0 ? zero : st.s[kb]);
-      else st.dp[kb] = mfma32(abuf[M % NBUF], dob[ks & 1], ks == 0 ? zero : st.dp[kb]);
+      else st.dp[kb] = mfma32(abuf[M % NBUF], dob[ks & 1], ks == 0 ? st.ndelta : st.dp[kb]);
     }
   }
   template <int M>
@@ -164,7 +166,7 @@ SP_DEV void dq_matrix_phase(const TrBase<D>& lo_kt, const RpBase<D>& lo_k, const
   ph.run();
 }
 
-// dS^T = p (dP^T - delta) with p = exp2(c S^T - lse2) on visible pairs; `hook(i)`, i = 0..3, is called at
+// dS^T = p (dP^T - delta) with p = exp2(c S^T - lse2) on visible pairs (`dp` arrives as dP^T - delta); `hook(i)`, i = 0..3, is called at
 // four points spread over the phase (asynchronous tile copies ride there).
 template <int D, int BN, class H>
 SP_DEV void dq_vector_phase(DqState<D, BN>& st, float c, bool need_mask, int kmin_rel, int kmax_rel, int g, H&& hook) {
@@ -189,7 +191,7 @@ SP_DEV void dq_vector_phase(DqState<D, BN>& st, float c, bool need_mask, int kmi
 #pragma unroll
       for (int i = 8 * half; i < 8 * half + 8; ++i) {
         const float p = exp2_fast(__builtin_fmaf(st.s[kb][i], c, -st.lse2));
-        st.s[kb][i] = p * (st.dp[kb][i] - st.delta);
+        st.s[kb][i] = p * st.dp[kb][i];          // dp arrives as dP - delta
       }
       st.ds[kb][half] = pack8(st.s[kb], 8 * half);
       // pin: without a use here the optimiser sinks this arithmetic past the phase barrier
@@ -224,7 +226,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
     for (int ks = 0; ks < KS; ++ks) st.qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks + 8 * g);
     const int64_t stat = ((int64_t)b * a.n_q_heads + h) * a.s_q + myrow_c;
     st.lse2 = a.lse2[stat];          // +inf for an empty row -> p = 0
-    st.delta = -a.delta[stat];       // (stored negated)
+    const float nd = a.delta[stat];  // (stored negated)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) st.ndelta[i] = nd;
   }
 #pragma unroll
   for (int db = 0; db < DB; ++db)
