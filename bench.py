@@ -224,7 +224,7 @@ def schedule_sim(spec, n, nrun, slices, step, torch):
     """Per-slice attention times of this GPU (events on the stream the calls go to, after each slice's forward
     call and each slice's backward call, inside one more pass of the step) -> what the paper's schedule makes of
     them: bubble fraction without the context exchange and with it, accumulated activation (Sec. 4.1.3, 4.2)."""
-    from paper_2504_14519_amd.schedule_sim import simulate, accumulated_fraction
+    from paper_2504_14519_amd.schedule_sim import simulate, simulate_lockstep, accumulated_fraction
     p_dev, m_mb = (int(x) for x in spec.split(","))
     if nrun != n or slices[0] != 0:
         return {"error": "needs a workload that runs every slice"}
@@ -248,6 +248,11 @@ def schedule_sim(spec, n, nrun, slices, step, torch):
     for mode in (None, "pairwise", "balanced", "ideal"):
         r = simulate(p_dev, n, m_mb, t["F"], t["B"], exchange=mode)
         res["bubble_fraction"][mode or "no_exchange"] = round(r["bubble_fraction"], 5)
+    # the same with aligned columns of passes (each as long as its slowest pass): bubble of the last device
+    res["lockstep_last_device_bubble_fraction"] = {
+        (mode or "no_exchange"): round(simulate_lockstep(p_dev, n, m_mb, t["F"], t["B"], exchange=mode)["bubble_fraction"][-1], 5)
+        for mode in (None, "pairwise", "balanced", "ideal")}
+    res["long_context_figure_(p-1)p/((n+1)nm)"] = round((p_dev - 1.0) * p_dev / ((n + 1.0) * n * m_mb), 5)
     return res
 
 

@@ -140,3 +140,35 @@ def simulate(p, n, m, t_fwd, t_bwd, exchange=None, t_other_fwd=0.0, t_other_bwd=
     ideal = sum(busy) / p
     return dict(makespan=makespan, busy=busy, bubble_fraction=(makespan - ideal) / ideal, timeline=timeline,
                 peak_slices=[accumulated_slices(p, n, m, r) for r in range(p)])
+
+
+def simulate_lockstep(p, n, m, t_fwd, t_bwd, exchange=None, partial_columns=False, t_other_fwd=0.0, t_other_bwd=0.0):
+    """The schedule as the paper draws it: passes that stand in one column (exchange_groups) start together and
+    the column lasts as long as its slowest pass.  This is the model behind the closed forms of Sec. 4.1.3: a
+    device's bubble is the sum of the columns in which it has no pass (p-1 forward columns and p-1 backward
+    columns), plus what it waits inside the columns it shares.
+
+    exchange: None, or 'pairwise' / 'balanced' / 'ideal' as in `simulate`; it is applied to the columns in which
+    all p devices have a pass (the situation of the paper's picture) and, with partial_columns, also among the
+    devices of the incomplete columns of the warm-up and cool-down.  With pass time proportional to the load
+    the paper's long-context bubble figure (p-1)p/((n+1)nm) lies between the last device's bubble in the two
+    variants: it charges the columns the last device is absent from at their heaviest pass, and nothing for the
+    incomplete columns it takes part in.
+
+    -> dict(makespan, busy[rank], bubble[rank], ideal, bubble_fraction[rank]) with ideal = all work spread evenly
+    over the p devices and bubble_fraction = bubble / ideal."""
+    plan = {None: None, "pairwise": redistribute_pairwise, "balanced": redistribute_balanced, "ideal": "ideal"}[exchange]
+    busy = [0.0] * p
+    makespan = 0.0
+    for (kind, _), members in exchange_groups(p, n, m).items():
+        loads = [i + 1 for _, _, i in members]
+        if plan is not None and (len(members) == p or partial_columns):
+            loads = [sum(loads) / float(len(loads))] * len(loads) if plan == "ideal" else plan(loads)[1]
+        table, other = (t_fwd, t_other_fwd) if kind == "F" else (t_bwd, t_other_bwd)
+        times = [pass_time(table, load) + other for load in loads]
+        makespan += max(times)
+        for (r, _, _), t in zip(members, times):
+            busy[r] += t
+    ideal = sum(busy) / p
+    bubble = [makespan - b for b in busy]
+    return dict(makespan=makespan, busy=busy, bubble=bubble, ideal=ideal, bubble_fraction=[b / ideal for b in bubble])

@@ -124,3 +124,34 @@ def test_exchange_conserves_blocks_and_dependencies_hold():
 def test_pass_time_interpolates():
     t = [1.0, 3.0, 7.0]
     assert pass_time(t, 2) == 3.0 and pass_time(t, 2.0) == 3.0 and abs(pass_time(t, 2.25) - 4.0) < 1e-12
+
+
+def test_lockstep_model_and_the_long_context_figure():
+    """Columns of aligned passes, each as long as its slowest pass: exact (p-1)/(nm) on every device for
+    slice-independent times; for pass time proportional to the attended key-value length the paper's
+    (p-1)p/((n+1)nm) is bracketed by the last device's bubble with and without the exchange in the incomplete
+    columns of warm-up and cool-down."""
+    from paper_2504_14519_amd.schedule_sim import simulate_lockstep
+    for p, n, m in [(2, 2, 1), (4, 8, 4), (4, 16, 2), (8, 32, 8), (8, 64, 2), (16, 64, 3)]:
+        u = simulate_lockstep(p, n, m, [0.7] * n, [1.9] * n)
+        for frac in u["bubble_fraction"]:
+            assert abs(frac - (p - 1.0) / (n * m)) < 1e-12
+        assert abs(u["makespan"] - (n * m + p - 1) * 2.6) < 1e-9
+        tf = [float(L) for L in range(1, n + 1)]
+        tb = [2.0 * L for L in range(1, n + 1)]
+        paper = (p - 1.0) * p / ((n + 1.0) * n * m)
+        full_only = simulate_lockstep(p, n, m, tf, tb, exchange="ideal")
+        everywhere = simulate_lockstep(p, n, m, tf, tb, exchange="ideal", partial_columns=True)
+        lo, hi = everywhere["bubble_fraction"][-1], full_only["bubble_fraction"][-1]
+        assert lo <= paper + 1e-12 and paper <= hi + 1e-12, (p, n, m, lo, paper, hi)
+        # the two ends in closed form: columns without the last device at their mean / heaviest pass, and the
+        # waits of the last device in the incomplete columns it shares
+        assert abs(lo - (p - 1.0) * (p + 2) / (2.0 * m * n * (n + 1))) < 1e-12
+        waits = sum(j * (1.0 + 2.0) for j in range(1, p - 1))          # it is j slices lighter than the heaviest
+        assert abs(hi - (paper + waits / (m * 3.0 * n * (n + 1) / 2.0))) < 1e-12
+        # the exchange conserves work; without it the columns last as long as their heaviest pass
+        plain = simulate_lockstep(p, n, m, tf, tb)
+        assert abs(sum(plain["busy"]) - sum(full_only["busy"])) < 1e-6
+        assert plain["makespan"] > full_only["makespan"] or p == 1
+        if n >= 2 * p:
+            assert plain["bubble_fraction"][-1] > 3 * hi
