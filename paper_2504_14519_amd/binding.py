@@ -37,8 +37,14 @@ def library_path():
 
 def _load():
     if not os.path.exists(_LIB_PATH):
-        raise ImportError("libslimpipe_attn.so is not built: run `python -m paper_2504_14519_amd.build` "
-                          "(there is no fallback path)")
+        # nothing built yet: compile the HIP library now (hipcc cross-compiles without a GPU).  There is no
+        # fallback path: if that fails, so does the import.
+        try:
+            from .build import build as _build
+            _build()
+        except Exception as e:
+            raise ImportError("libslimpipe_attn.so is not built and building it failed (%s): run "
+                              "`python paper_2504_14519_amd/build.py`" % e)
     L = ctypes.CDLL(_LIB_PATH)
     P = ctypes.POINTER(AttnParams)
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
