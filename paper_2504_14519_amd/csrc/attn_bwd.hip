@@ -412,7 +412,8 @@ hipError_t launch_bwd_dq(const BwdArgs& a, int batch, int head_dim, hipStream_t 
 // keys (every query tile, for every head of the GQA group, in a fixed order: the sums are
 // reproducible) stream through LDS as tiles of 32 rows of Q and dO.  Per tile u a wave runs
 //   matrix phase MM(u): dV^T += dO(u-1)^T P(u-1),  dK^T += Q(u-1)^T dS(u-1)    (transposed reads)
-//                       S(u) = Q(u) K^T,  dP(u) = dO(u) V^T                     (row-packed reads)
+//                       S(u) = Q(u) K^T,  dP(u) = dO(u) V^T - delta              (row-packed reads; the
+//                       accumulator of dP starts from -delta, and lse2 of the tile is fetched on the way)
 //   vector phase VV(u): P = exp2(c S - lse2),  dS = P (dP - delta), packed to bf16
 // and the two wave groups run one phase apart exactly as in the dq kernel.  (One wave per SIMD with
 // twice the registers cannot overlap the two kinds of work: a wave that has issued an MFMA issues
