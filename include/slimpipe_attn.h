@@ -7,12 +7,13 @@
  * in reverse order.  Any call may be restricted to a key range [kv_begin, kv_end); it then
  * returns the partial output together with the softmax normaliser of that range, which is what
  * the paper's attention context exchange (Sec. 4.2.2) and commutated context parallelism
- * (Sec. 5) ship between devices and fold together "by the online softmax method".
+ * (Sec. 5) ship between devices and fold together with the online-softmax merge rule.
  *
  * Conventions
  *   - All data pointers are DEVICE pointers owned by the caller.  The library allocates nothing on
- *     the device, keeps no state between calls (but for the optional profiling switch below), enqueues its kernels on the caller's HIP stream
- *     (a hipStream_t passed as void*, NULL = default stream) and returns without synchronising.
+ *     the device, keeps no state between calls (but for the optional profiling switch below), enqueues
+ *     its kernels on the caller's HIP stream (a hipStream_t passed as void*, NULL = default stream) and
+ *     returns without synchronising.
  *   - q, out, d_out, dq:  [batch, s_q, n_q_heads, head_dim], element strides given, head_dim contiguous.
  *   - k, v, dk_acc, dv_acc: [batch, kv_capacity, n_kv_heads, head_dim]; row j of the prefix IS global
  *     key position j (the base pointer is position 0).

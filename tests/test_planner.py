@@ -1,5 +1,5 @@
 """Host-side planner of the attention context exchange (paper Sec. 4.2.2) against what the paper fixes:
-the worked picture (Fig. attn_balance), the "at most one slice" claim, the slice counts that enter the
+the worked picture (Fig. attn_balance), the claim that loads end within one key-value slice of each other, the slice counts that enter the
 communication-volume formula and its bound.  CPU only."""
 import json
 import os
