@@ -11,9 +11,13 @@
  *
  * Conventions
  *   - All data pointers are DEVICE pointers owned by the caller.  The library allocates nothing on
- *     the device, keeps no state between calls (but for the optional profiling switch below), enqueues
- *     its kernels on the caller's HIP stream (a hipStream_t passed as void*, NULL = default stream) and
- *     returns without synchronising.
+ *     the device, enqueues its kernels on the caller's HIP stream (a hipStream_t passed as void*,
+ *     NULL = default stream) and returns without synchronising.
+ *   - State.  Per device the library remembers two facts that depend on the device alone: that its
+ *     kernels have been allowed their dynamic LDS (done once, see slimpipe_attn_init) and the number of
+ *     compute units.  Both are set under a once-flag / atomically, so the entry points may be called from
+ *     several host threads at once (each with its own stream and buffers).  Nothing else persists
+ *     between calls; the measurement aids of slimpipe_attn_bench.h keep their own records.
  *   - q, out, d_out, dq:  [batch, s_q, n_q_heads, head_dim], element strides given, head_dim contiguous.
  *   - k, v, dk_acc, dv_acc: [batch, kv_capacity, n_kv_heads, head_dim]; row j of the prefix IS global
  *     key position j (the base pointer is position 0).
@@ -71,6 +75,14 @@ typedef struct slimpipe_attn_params {
   int64_t o_stride_b, o_stride_s, o_stride_h;     /* out                                   */
   int64_t do_stride_b, do_stride_s, do_stride_h;  /* d_out (backward only)                 */
 } slimpipe_attn_params;
+
+/* Prepares the CURRENT device (hipSetDevice) for launches: allows every kernel of the library the dynamic LDS
+ * it uses (more than the 64 KB a kernel gets by default).  Thread-safe, idempotent, a few microseconds after
+ * the first call.  Every launching entry point does the same on its first call on a device, so calling this is
+ * optional - except before HIP graph capture: the attribute call is not a stream operation and must have happened
+ * before a capture begins, so call slimpipe_attn_init() once per device first; after it a capture needs no
+ * eager warm-up launch.  Returns SLIMPIPE_OK or SLIMPIPE_ELAUNCH. */
+int slimpipe_attn_init(void);
 
 /* Host-only argument check shared by every entry point (is_bwd != 0 also checks what only the
  * backward needs).  No device access. */
@@ -133,7 +145,10 @@ int slimpipe_attn_merge(int32_t n_parts, const void* const* outs, const float* c
                         void* hip_stream);
 
 /* Round float32 accumulators (dk_acc/dv_acc after the last slice's backward) to bf16, RNE.
- * Contiguous, n_elems elements. */
+ * Contiguous, n_elems elements.  The paper trains in bf16 and says nothing of the precision in which the
+ * key/value gradients of the slices of a sequence are added up (Sec. 4.1.2 only fixes that the backward passes
+ * run slice by slice); the reading taken here: float32 accumulators across the calls, in call order, and ONE
+ * rounding to bf16 at the end, which is this call. */
 int slimpipe_attn_finalize_bf16(const float* acc, void* dst_bf16, int64_t n_elems, void* hip_stream);
 
 /* The same two calls with the cached keys / values given the way the paper stores them (Sec. 5): a list
@@ -176,25 +191,6 @@ int slimpipe_attn_fwd_ranges(const slimpipe_attn_params* p, const void* q_slice,
                              float* part_out, float* part_lse, void* out, float* lse, void* hip_stream);
 
 const char* slimpipe_attn_strerror(int code);
-
-/* Optional per-kernel timing for benchmarks (not part of the paper's method).  While enabled, every
- * kernel the library enqueues is bracketed by HIP events recorded on the caller's stream.
- * slimpipe_attn_profile_read waits for the recorded events, adds up the elapsed time per kernel kind
- * since the last read and clears the records.  The only state the library keeps; not thread-safe. */
-enum {
-  SLIMPIPE_KERNEL_FWD = 0, SLIMPIPE_KERNEL_DELTA = 1, SLIMPIPE_KERNEL_DQ = 2, SLIMPIPE_KERNEL_DKDV = 3,
-  SLIMPIPE_KERNEL_MERGE = 4, SLIMPIPE_KERNEL_FINALIZE = 5, SLIMPIPE_KERNEL_DKDV_REDUCE = 6,
-  SLIMPIPE_KERNEL_DQ_REDUCE = 7, SLIMPIPE_KERNEL_KINDS = 8
-};
-int slimpipe_attn_profile_enable(int enable);
-int slimpipe_attn_profile_read(double total_ms[SLIMPIPE_KERNEL_KINDS], int64_t launches[SLIMPIPE_KERNEL_KINDS]);
-
-/* Measurement aid for benchmarks (not part of the paper's method): the rate, in TFLOP/s, at which this
- * GPU sustains a pure stream of the bf16 MFMA instruction the attention kernels use, with constant
- * operands (random_operands == 0) or with random ones (!= 0), under which the chip is power limited
- * and clocks lower.  Runs two short kernels (about 20 ms each) on the stream and waits for them.
- * sink: device pointer to at least one float (never written in practice). */
-int slimpipe_attn_mfma_rate(int random_operands, float* sink, double* tflops, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -48,6 +48,8 @@ def _load():
     L = ctypes.CDLL(_LIB_PATH)
     P = ctypes.POINTER(AttnParams)
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    L.slimpipe_attn_init.argtypes = []
+    L.slimpipe_attn_init.restype = ctypes.c_int
     L.slimpipe_attn_validate.argtypes = [P, ctypes.c_int]
     L.slimpipe_attn_validate.restype = ctypes.c_int
     L.slimpipe_attn_workspace_bytes.argtypes = [P, ctypes.c_int, ctypes.POINTER(ctypes.c_size_t)]
@@ -114,6 +116,11 @@ def make_params(q, k, out_like, q_offset, kv_begin, kv_end, causal, scale, out_d
     p.o_stride_b, p.o_stride_s, p.o_stride_h = out_like.stride(0), out_like.stride(1), out_like.stride(2)
     p.do_stride_b, p.do_stride_s, p.do_stride_h = p.o_stride_b, p.o_stride_s, p.o_stride_h   # backward overrides
     return p
+
+
+def slimpipe_attn_init():
+    """Prepare the current device for launches (needed once per device before a HIP graph capture)."""
+    _check(lib.slimpipe_attn_init(), "slimpipe_attn_init")
 
 
 def slimpipe_attn_validate(params, is_bwd=False):

@@ -2,9 +2,12 @@
 #include <math.h>
 #include <string.h>
 
+#include <atomic>
+#include <mutex>
 #include <vector>
 
 #include "../../include/slimpipe_attn.h"
+#include "../../include/slimpipe_attn_bench.h"
 #include "kernels.hpp"
 
 using namespace slimpipe;
@@ -21,15 +24,39 @@ size_t stat_bytes(const slimpipe_attn_params* p) {
 }
 size_t delta_bytes(const slimpipe_attn_params* p) { return 2 * stat_bytes(p); }
 
-// Compute units of the current device (256 on MI355X, also assumed when no device can be asked).
+// ---- per-device state: the only state the library keeps besides the benchmark's profiling switch ----
+// For each device the dynamic-LDS opt-in of the kernels (done once, under std::call_once) and the number of
+// compute units.  Both are functions of the device alone, so concurrent callers agree on them.
+constexpr int kMaxDevices = 64;
+struct DeviceState {
+  std::once_flag once;
+  hipError_t status = hipSuccess;
+};
+DeviceState g_device[kMaxDevices];
+std::atomic<int> g_compute_units[kMaxDevices];
+
+// Makes the current device ready for launches: SLIMPIPE_OK, or SLIMPIPE_ELAUNCH when the runtime refuses.
+int ensure_device_ready() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SLIMPIPE_ELAUNCH;
+  DeviceState& d = g_device[dev];
+  std::call_once(d.once, [&d] {
+    d.status = opt_in_fwd_kernels();
+    if (d.status == hipSuccess) d.status = opt_in_bwd_kernels();
+  });
+  return d.status == hipSuccess ? SLIMPIPE_OK : SLIMPIPE_ELAUNCH;
+}
+
+// Compute units of the current device (256 on MI355X, also assumed when no device can be asked, so that the
+// workspace query stays a pure host function).
 int compute_units() {
-  static const int n = [] {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 256;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
-    return cus;
-  }();
-  return n;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+  int cus = g_compute_units[dev].load(std::memory_order_relaxed);
+  if (cus > 0) return cus;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+  g_compute_units[dev].store(cus, std::memory_order_relaxed);
+  return cus;
 }
 
 // The dk/dv kernel runs one workgroup per compute unit; a call with W key tiles takes ceil(W / CUs)
@@ -93,7 +120,8 @@ int fwd_preferred_ranges(const slimpipe_attn_params* p) {
   const int cus = compute_units();
   double best = 1e30, cost[kMaxRanges + 1];
   for (int r = 1; r <= kMaxRanges; ++r) {
-    cost[r] = (r > 1 && keys / r < 1024) ? 1e30 : (double)((w * r + cus - 1) / cus) / r;
+    // (a range keeps at least 1024 keys; batch * ranges is the grid's z dimension)
+    cost[r] = (r > 1 && (keys / r < 1024 || (int64_t)p->batch * r > 65535)) ? 1e30 : (double)((w * r + cus - 1) / cus) / r;
     if (cost[r] < best) best = cost[r];
   }
   for (int r = 1; r <= kMaxRanges; ++r)
@@ -146,13 +174,14 @@ int check_chunks(const slimpipe_attn_params* p, int32_t n_chunks, int64_t chunk_
 
 
 
-// ---- optional per-kernel event timing -------------------------------------------------------
+// ---- optional per-kernel event timing (benchmark aid) ----------------------------------------------
 struct ProfRecord { int kind; hipEvent_t start, stop; };
-bool g_prof_on = false;
+std::atomic<bool> g_prof_on{false};
+std::mutex g_prof_mutex;                     // guards the two vectors
 std::vector<ProfRecord> g_prof_records;
 std::vector<hipEvent_t> g_prof_free;
 
-hipEvent_t prof_event() {
+hipEvent_t prof_event() {                    // (caller holds g_prof_mutex)
   if (!g_prof_free.empty()) { hipEvent_t e = g_prof_free.back(); g_prof_free.pop_back(); return e; }
   hipEvent_t e = nullptr;
   if (hipEventCreate(&e) != hipSuccess) return nullptr;
@@ -161,7 +190,8 @@ hipEvent_t prof_event() {
 
 template <class F>
 hipError_t timed(int kind, hipStream_t st, F&& launch) {
-  if (!g_prof_on) return launch();
+  if (!g_prof_on.load(std::memory_order_relaxed)) return launch();
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
   ProfRecord r{kind, prof_event(), prof_event()};
   if (!r.start || !r.stop) return launch();
   (void)hipEventRecord(r.start, st);
@@ -175,8 +205,10 @@ hipError_t timed(int kind, hipStream_t st, F&& launch) {
 
 extern "C" {
 
+int slimpipe_attn_init(void) { return ensure_device_ready(); }
+
 int slimpipe_attn_profile_enable(int enable) {
-  g_prof_on = enable != 0;
+  g_prof_on.store(enable != 0, std::memory_order_relaxed);
   return SLIMPIPE_OK;
 }
 
@@ -184,6 +216,7 @@ int slimpipe_attn_profile_read(double total_ms[SLIMPIPE_KERNEL_KINDS], int64_t l
   if (!total_ms || !launches) return SLIMPIPE_EINVAL_NULL;
   for (int i = 0; i < SLIMPIPE_KERNEL_KINDS; ++i) { total_ms[i] = 0.0; launches[i] = 0; }
   int rc = SLIMPIPE_OK;
+  std::lock_guard<std::mutex> lock(g_prof_mutex);
   for (const ProfRecord& r : g_prof_records) {
     float ms = 0.f;
     if (hipEventSynchronize(r.stop) != hipSuccess || hipEventElapsedTime(&ms, r.start, r.stop) != hipSuccess)
@@ -291,6 +324,7 @@ static int fwd_impl(const slimpipe_attn_params* p, const void* q_slice, const vo
     a.out_range_stride = 0; a.lse_range_stride = 0;
     a.o_stride_b = p->o_stride_b; a.o_stride_s = p->o_stride_s; a.o_stride_h = p->o_stride_h;
   }
+  if (ensure_device_ready() != SLIMPIPE_OK) return SLIMPIPE_ELAUNCH;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipError_t e = timed(SLIMPIPE_KERNEL_FWD, st, [&] { return launch_fwd(a, p->batch, p->head_dim, st); });
   if (e != hipSuccess) return SLIMPIPE_ELAUNCH;
@@ -319,7 +353,7 @@ static int fwd_auto(const slimpipe_attn_params* p, const void* q_slice, const vo
   int rc = slimpipe_attn_validate(p, 0);
   if (rc != SLIMPIPE_OK) return rc;
   int ranges = workspace ? fwd_preferred_ranges(p) : 1;
-  while (ranges > 1 && fwd_parts_bytes(p, ranges) > workspace_bytes) --ranges;
+  while (ranges > 1 && (fwd_parts_bytes(p, ranges) > workspace_bytes || (int64_t)p->batch * ranges > 65535)) --ranges;
   if (ranges <= 1)
     return fwd_impl(p, q_slice, k_chunks, v_chunks, n_chunks, chunk_len, 1, &p->kv_begin, &p->kv_end, nullptr, 0, nullptr, 0, out,
                     lse, hip_stream);
@@ -404,7 +438,7 @@ static int bwd_impl(const slimpipe_attn_params* p, const void* q_slice, const vo
   // what is left of the workspace takes the partial dq of as many key ranges as fit
   const size_t used = delta_bytes(p) + split_bytes(p, n_chunks, split);
   int dq_ranges = fwd_preferred_ranges(p);
-  while (dq_ranges > 1 && used + dq_parts_bytes(p, dq_ranges) > workspace_bytes) --dq_ranges;
+  while (dq_ranges > 1 && (used + dq_parts_bytes(p, dq_ranges) > workspace_bytes || (int64_t)p->batch * dq_ranges > 65535)) --dq_ranges;
   a.n_dq_ranges = dq_ranges;
   for (int r = 0; r < kMaxRanges; ++r) a.dq_range_begin[r] = a.dq_range_end[r] = 0;
   if (dq_ranges > 1) {
@@ -431,6 +465,7 @@ static int bwd_impl(const slimpipe_attn_params* p, const void* q_slice, const vo
   a.kv_stride_b = p->kv_stride_b; a.kv_stride_s = p->kv_stride_s; a.kv_stride_h = p->kv_stride_h;
   a.o_stride_b = p->o_stride_b; a.o_stride_s = p->o_stride_s; a.o_stride_h = p->o_stride_h;
   a.do_stride_b = p->do_stride_b; a.do_stride_s = p->do_stride_s; a.do_stride_h = p->do_stride_h;
+  if (ensure_device_ready() != SLIMPIPE_OK) return SLIMPIPE_ELAUNCH;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (timed(SLIMPIPE_KERNEL_DELTA, st, [&] { return launch_delta(a, p->batch, p->head_dim, st); }) != hipSuccess) return SLIMPIPE_ELAUNCH;
   if (timed(SLIMPIPE_KERNEL_DQ, st, [&] { return launch_bwd_dq(a, p->batch, p->head_dim, st); }) != hipSuccess) return SLIMPIPE_ELAUNCH;

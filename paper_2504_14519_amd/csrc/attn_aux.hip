@@ -34,7 +34,9 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const MergeArgs a) {
   if (has) {
     const float inv = 1.0f / tot;
     for (int p = 0; p < a.n_parts; ++p) {
-      const float w = exp2_fast((a.lses[p][sidx] - m) * kLog2e) * inv;
+      const float lp = a.lses[p][sidx];
+      if (lp == -INFINITY) continue;          // weight 0: the part's out row is not read (it may be uninitialised)
+      const float w = exp2_fast((lp - m) * kLog2e) * inv;
       if (a.part_f32) {
         const f32x4* src = reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(a.outs[p]) + eoff);
         const f32x4 x0 = src[0], x1 = src[1];

@@ -13,10 +13,6 @@
 //     group in a fixed order: S = Q K^T, dP = dO V^T land with one key per lane and 16 query rows
 //     in the registers, which is the B operand of dV^T += dO^T P and dK^T += Q^T dS.
 //     One workgroup owns a key row outright, so dK/dV are bit-reproducible.
-#include <stdlib.h>
-
-#include <type_traits>
-
 #include "kernels.hpp"
 #include "tile_common.hpp"
 
@@ -328,30 +324,18 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
     };
     // Both groups run the same code; group B starts one phase (one barrier) later and group A idles
     // one phase at the end.  Group A copies K tiles, group B V tiles.
-#ifdef SLIMPIPE_TRACE
-    long long tq_v = 0, tq_b1 = 0, tq_m = 0, tq_w = 0, tq_b2 = 0, tq_t0 = clock64(), tq_w0 = wall_clock64(), tq_last = clock64();
-#define TQ_MARK(var) { long long _n = clock64(); var += _n - tq_last; tq_last = _n; }
-#else
-#define TQ_MARK(var)
-#endif
     if (group_b) phase_end();
     dq_matrix_phase<D, BN, false, true>(lo_kt, lo_k, lo_v, lo_do, st);       // scores of tile 0
     advance();
     wait_async();
     phase_end();
-    TQ_MARK(tq_b2)
     for (int u = 0; u + 1 < nt; ++u) {
       vector_phase(u, make_copy(u + 2));                 // tile u+2 rides along
-      TQ_MARK(tq_v)
       phase_end();
-      TQ_MARK(tq_b1)
       dq_matrix_phase<D, BN, true, true>(lo_kt, lo_k, lo_v, lo_do, st);      // dQ of tile u, scores of tile u+1
       advance();
-      TQ_MARK(tq_m)
       wait_async();                                      // the copies of the vector phase before have landed
-      TQ_MARK(tq_w)
       phase_end();
-      TQ_MARK(tq_b2)
     }
     vector_phase(nt - 1, make_copy(nt + 1));             // (copies the last tile once more)
     phase_end();
@@ -359,13 +343,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
     wait_async();
     phase_end();
     if (!group_b) phase_end();
-#ifdef SLIMPIPE_TRACE
-    if (blockIdx.x == gridDim.x - 1 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {
-      long long* dbg = reinterpret_cast<long long*>(a.lse2 + (int64_t)a.n_q_heads * a.s_q) + 8;   // behind the workspace proper
-      dbg[0] = tq_v; dbg[1] = tq_b1; dbg[2] = tq_m; dbg[3] = tq_w; dbg[4] = tq_b2;
-      dbg[5] = clock64() - tq_t0; dbg[6] = wall_clock64() - tq_w0; dbg[7] = nt;
-    }
-#endif
   }
 
   const int tid_out = fresh(tid), myrow_out = wrow0 + (tid_out & 31), g_out = (tid_out >> 5) & 1;
@@ -390,20 +367,22 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
   }
 }
 
+constexpr int kDqKeysPerTile = 64;
+template <int D>
+constexpr size_t dq_lds_bytes() { return (size_t)6 * kDqKeysPerTile * D * 2 + (size_t)256 * D * 2; }   // 4 K slots + 2 V slots + dO rows
+
 template <int D, int NW, int BN>
 static hipError_t launch_dq_t(const BwdArgs& a, int batch, hipStream_t st) {
   constexpr int BM = NW * 32;
-  const size_t smem = (size_t)6 * BN * D * 2 + (size_t)BM * D * 2;   // 4 K slots + 2 V slots + dO rows
-  static LdsOptIn opt_in;
-  if (hipError_t e = opt_in.ensure(reinterpret_cast<const void*>(&attn_bwd_dq_kernel<D, NW, BN>), smem); e != hipSuccess) return e;
+  static_assert(BM == 256 && BN == kDqKeysPerTile, "dq_lds_bytes assumes this shape");
   dim3 grid((a.s_q + BM - 1) / BM, a.n_q_heads, batch * a.n_dq_ranges), block(NW * 64);
-  hipLaunchKernelGGL((attn_bwd_dq_kernel<D, NW, BN>), grid, block, smem, st, a);
+  hipLaunchKernelGGL((attn_bwd_dq_kernel<D, NW, BN>), grid, block, dq_lds_bytes<D>(), st, a);
   return hipGetLastError();
 }
 
 hipError_t launch_bwd_dq(const BwdArgs& a, int batch, int head_dim, hipStream_t st) {
-  if (head_dim == 128) return launch_dq_t<128, 8, 64>(a, batch, st);
-  return launch_dq_t<64, 8, 64>(a, batch, st);
+  if (head_dim == 128) return launch_dq_t<128, 8, kDqKeysPerTile>(a, batch, st);
+  return launch_dq_t<64, 8, kDqKeysPerTile>(a, batch, st);
 }
 
 // ------------------------------------------------------------------------------------ dk / dv
@@ -784,12 +763,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
       const float* stat = reinterpret_cast<const float*>(smem + L::STAT_BASE + vslot * L::STAT_BYTES);
       dkdv_vector_phase<D>(st, stat, c, need_mask, rmin_rel, rmax_rel, (fresh(tid) >> 5) & 1, [&](int part) { copy_part(j, copies_q, part); });
     };
-#ifdef SLIMPIPE_TRACE
-    long long tr_v = 0, tr_b1 = 0, tr_m = 0, tr_w = 0, tr_b2 = 0, tr_t0 = clock64(), tr_w0 = wall_clock64(), tr_last = clock64();
-#define TR_MARK(var) { long long _n = clock64(); var += _n - tr_last; tr_last = _n; }
-#else
-#define TR_MARK(var)
-#endif
     // Both groups run the same code; group B starts one phase (one barrier) later and group A idles
     // one phase at the end.
     if (group_b) phase_end();
@@ -797,7 +770,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     advance();
     wait_async();
     phase_end();
-    TR_MARK(tr_b2)
     // (a fresh live range for K right in front of the loop: if the register allocator had to park part of
     // it in scratch memory during the prologue, it comes back here and not inside the loop)
 #pragma unroll
@@ -811,18 +783,13 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
       row0_nxt = row0_new;
       vslot = (vslot + 1) & (SLOTS - 1);
       cslot = (cslot + 1) & (SLOTS - 1);
-      TR_MARK(tr_v)
       phase_end();
-      TR_MARK(tr_b1)
       // (V never moves: without this the eight offsets of its head_dim blocks are kept in registers across the loop)
       asm volatile("" : "+v"(lo_v.off0));
       { DkdvMatrixPhase<D, NW, true, true, 2> ph{lo_qt, lo_q, lo_v, st, stat_of(vslot)}; ph.run(); }    // sums of tile u, scores of tile u+1
       advance();
-      TR_MARK(tr_m)
       wait_async();                                      // the copies of the vector phase before have landed
-      TR_MARK(tr_w)
       phase_end();
-      TR_MARK(tr_b2)
     }
     vector_phase(cnt - 1, vslot, row0_cur, make_copy(cc, cslot));   // (copies the last tile once more)
     phase_end();
@@ -830,13 +797,6 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     wait_async();
     phase_end();
     if (!group_b) phase_end();
-#ifdef SLIMPIPE_TRACE
-    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {
-      long long* dbg = reinterpret_cast<long long*>(a.lse2 + (int64_t)a.n_q_heads * a.s_q);   // behind the workspace proper
-      dbg[0] = tr_v; dbg[1] = tr_b1; dbg[2] = tr_m; dbg[3] = tr_w; dbg[4] = tr_b2;
-      dbg[5] = clock64() - tr_t0; dbg[6] = wall_clock64() - tr_w0; dbg[7] = cnt;
-    }
-#endif
   }
 
   // (the key is worked out afresh from an opaque copy of the lane number: otherwise its 64 bits stay in
@@ -935,14 +895,21 @@ __global__ __launch_bounds__(256) void dq_reduce_kernel(const BwdArgs a, int bat
 template <int D, int NW>
 static hipError_t launch_dkdv_t(const BwdArgs& a, int batch, hipStream_t st) {
   constexpr int BNK = NW * 32;
-  const size_t smem = DkdvLds<D, NW>::TOTAL;
-  static LdsOptIn opt_in;
-  if (hipError_t e = opt_in.ensure(reinterpret_cast<const void*>(&attn_bwd_dkdv_kernel<D, NW>), smem); e != hipSuccess) return e;
   if (a.kv_end <= a.kv_begin) return hipSuccess;
   const int64_t nkeys = a.kv_end - kv_grid_origin(a.kv_begin, a.kv.n, BNK);
   dim3 grid((unsigned)((nkeys + BNK - 1) / BNK) * (unsigned)a.n_split, a.n_kv_heads, batch), block(NW * 64);
+  constexpr size_t smem = DkdvLds<D, NW>::TOTAL;
   hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, NW>), grid, block, smem, st, a);
   return hipGetLastError();
+}
+
+hipError_t opt_in_bwd_kernels() {
+  const hipFuncAttribute attr = hipFuncAttributeMaxDynamicSharedMemorySize;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dq_kernel<128, 8, kDqKeysPerTile>), attr, (int)dq_lds_bytes<128>());
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dq_kernel<64, 8, kDqKeysPerTile>), attr, (int)dq_lds_bytes<64>());
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dkdv_kernel<128, 8>), attr, DkdvLds<128, 8>::TOTAL);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dkdv_kernel<64, 8>), attr, DkdvLds<64, 8>::TOTAL);
+  return e;
 }
 
 hipError_t launch_bwd_dkdv(const BwdArgs& a, int batch, int head_dim, hipStream_t st) {

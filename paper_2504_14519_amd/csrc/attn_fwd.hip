@@ -17,15 +17,15 @@
 #include "kernels.hpp"
 #include "tile_common.hpp"
 
+namespace slimpipe {
+
 // Keys per tile of the forward kernel.  128 instead of 64 halves the per-tile bookkeeping and the number of phase
 // barriers per key (measured: 4 % less forward time); five 128-key tiles of head_dim 128 are the whole 160 KB of LDS.
-#ifndef SP_FWD_BN
-#define SP_FWD_BN 128
-#endif
-#define SP_FWD_RM_FIRST ((KB + 1) / 2)
-#define SP_FWD_LOOK 2
-
-namespace slimpipe {
+constexpr int kFwdKeysPerTile = 128;
+// operand look-ahead of the matrix phase (LDS reads issued this many MFMAs early)
+constexpr int kFwdLook = 2;
+// 32-key blocks of a tile whose row maxima are taken at the tail of the matrix phase (the rest: vector phase)
+constexpr int fwd_rowmax_first_blocks(int kb) { return (kb + 1) / 2; }
 
 template <int D, int BN>
 struct FwdState {
@@ -58,7 +58,7 @@ SP_DEV float fwd_rowmax_first(FwdState<D, BN>& st, bool need_mask, int kmin_rel,
   }
   float mx = -INFINITY;
 #pragma unroll
-  for (int kb = 0; kb < SP_FWD_RM_FIRST; ++kb)
+  for (int kb = 0; kb < fwd_rowmax_first_blocks(KB); ++kb)
 #pragma unroll
     for (int i = 0; i < 16; i += 2) mx = fmaxf(fmaxf(st.s[kb][i], st.s[kb][i + 1]), mx);
   return mx;
@@ -67,7 +67,7 @@ template <int D, int BN>
 SP_DEV float fwd_rowmax_rest(const FwdState<D, BN>& st, float mx) {
   constexpr int KB = BN / 32;
 #pragma unroll
-  for (int kb = SP_FWD_RM_FIRST; kb < KB; ++kb)
+  for (int kb = fwd_rowmax_first_blocks(KB); kb < KB; ++kb)
 #pragma unroll
     for (int i = 0; i < 16; i += 2) mx = fmaxf(fmaxf(st.s[kb][i], st.s[kb][i + 1]), mx);
   return xhalf_max(mx);
@@ -327,66 +327,55 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_kernel(const FwdArgs a) {
       kslot = (kslot == KSLOTS - 1) ? 0 : kslot + 1;
       vslot ^= 1;
     };
-#ifdef SLIMPIPE_TRACE
-    long long tp_v = 0, tp_w = 0, tp_b1 = 0, tp_m = 0, tp_b2 = 0, tp_t0 = clock64(), tp_w0 = wall_clock64(), tp_last = clock64();
-#define TP_MARK(var) { long long _n = clock64(); var += _n - tp_last; tp_last = _n; }
-#else
-#define TP_MARK(var)
-#endif
     // Both groups run the same code; group B starts one phase (one barrier) later and group A idles
     // one phase at the end.
     if (group_b) phase_end();
-    { FwdMatrixPhase<D, BN, false, true, SP_FWD_LOOK> ph{lo_v, lo_k, st}; ph.run(); }
+    { FwdMatrixPhase<D, BN, false, true, kFwdLook> ph{lo_v, lo_k, st}; ph.run(); }
     rowmax_tile(0);
     advance();
     wait_async();
     phase_end();
-    TP_MARK(tp_b2)
     for (int t = 0; t + 1 < nt; ++t) {
       vector_phase(make_copy(copies_k ? t + 2 : t + 1));
-      TP_MARK(tp_v)
       phase_end();
-      TP_MARK(tp_b1)
-      { FwdMatrixPhase<D, BN, true, true, SP_FWD_LOOK> ph{lo_v, lo_k, st}; ph.run(); }
+      { FwdMatrixPhase<D, BN, true, true, kFwdLook> ph{lo_v, lo_k, st}; ph.run(); }
       rowmax_tile(t + 1);
       advance();
-      TP_MARK(tp_m)
       wait_async();                                      // the copies of the vector phase before have landed
-      TP_MARK(tp_w)
       phase_end();
-      TP_MARK(tp_b2)
     }
     vector_phase(make_copy(copies_k ? nt + 1 : nt));
     phase_end();
-    { FwdMatrixPhase<D, BN, true, false, SP_FWD_LOOK> ph{lo_v, lo_k, st}; ph.run(); }
+    { FwdMatrixPhase<D, BN, true, false, kFwdLook> ph{lo_v, lo_k, st}; ph.run(); }
     wait_async();
     phase_end();
     if (!group_b) phase_end();
-#ifdef SLIMPIPE_TRACE
-    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && tid == 0) {
-      long long* dbg = reinterpret_cast<long long*>(a.lse + (int64_t)a.n_q_heads * a.s_q);   // caller over-allocates lse
-      dbg[0] = tp_v; dbg[1] = tp_w; dbg[2] = tp_b1; dbg[3] = tp_m; dbg[4] = 0; dbg[5] = tp_b2;
-      dbg[6] = clock64() - tp_t0; dbg[7] = wall_clock64() - tp_w0; dbg[8] = nt;
-    }
-#endif
   }
   fwd_epilogue<D, BN>(a, st, myrow, h, b, r, g);
 }
 
+template <int D>
+constexpr size_t fwd_lds_bytes() { return (size_t)5 * kFwdKeysPerTile * D * 2; }       // K ring of three, V ring of two
+
 template <int D, int NW, int BN>
 static hipError_t launch_fwd_t(const FwdArgs& a, int batch, hipStream_t st) {
   constexpr int BM = NW * 32;
-  const size_t smem = (size_t)5 * BN * D * 2;       // K ring of three, V ring of two
-  static LdsOptIn opt_in;
-  if (hipError_t e = opt_in.ensure(reinterpret_cast<const void*>(&attn_fwd_kernel<D, NW, BN>), smem); e != hipSuccess) return e;
   dim3 grid((a.s_q + BM - 1) / BM, a.n_q_heads, batch * a.n_ranges), block(NW * 64);
-  hipLaunchKernelGGL((attn_fwd_kernel<D, NW, BN>), grid, block, smem, st, a);
+  hipLaunchKernelGGL((attn_fwd_kernel<D, NW, BN>), grid, block, fwd_lds_bytes<D>(), st, a);
   return hipGetLastError();
 }
 
 hipError_t launch_fwd(const FwdArgs& a, int batch, int head_dim, hipStream_t st) {
-  if (head_dim == 128) return launch_fwd_t<128, 8, SP_FWD_BN>(a, batch, st);
-  return launch_fwd_t<64, 8, SP_FWD_BN>(a, batch, st);
+  if (head_dim == 128) return launch_fwd_t<128, 8, kFwdKeysPerTile>(a, batch, st);
+  return launch_fwd_t<64, 8, kFwdKeysPerTile>(a, batch, st);
+}
+
+hipError_t opt_in_fwd_kernels() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_kernel<128, 8, kFwdKeysPerTile>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)fwd_lds_bytes<128>());
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_kernel<64, 8, kFwdKeysPerTile>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)fwd_lds_bytes<64>());
 }
 
 }  // namespace slimpipe

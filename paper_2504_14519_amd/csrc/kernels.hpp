@@ -87,20 +87,11 @@ struct MergeArgs {
   int64_t o_stride_b, o_stride_s, o_stride_h;
 };
 
-// A kernel that uses more than 64 KB of dynamic LDS has to be told so once per device (the attribute
-// belongs to the function on the current device).  `done` is the caller's per-kernel record.
-struct LdsOptIn {
-  bool done[64] = {};
-  hipError_t ensure(const void* kernel, size_t bytes) {
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev >= 0 && dev < 64 && done[dev]) return hipSuccess;
-    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    if (e == hipSuccess && dev >= 0 && dev < 64) done[dev] = true;
-    return e;
-  }
-};
+// The attention kernels use more than 64 KB of dynamic LDS, which a kernel has to be allowed once per device
+// (hipFuncSetAttribute; the attribute belongs to the function on the CURRENT device).  These two set it for
+// every instantiation of the forward / backward kernels; api.hip calls them once per device.
+hipError_t opt_in_fwd_kernels();
+hipError_t opt_in_bwd_kernels();
 
 hipError_t launch_fwd(const FwdArgs& a, int batch, int head_dim, hipStream_t st);
 hipError_t launch_delta(const BwdArgs& a, int batch, int head_dim, hipStream_t st);

@@ -287,10 +287,7 @@ SP_DEV void wait_async() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 // this the younger group's MFMAs wait behind the vector instructions of the older group that shares
 // its SIMDs; a wave in a matrix phase issues only a handful of instructions per MFMA, so letting it
 // go first costs the vector phase little.
-#ifndef SP_MATRIX_PRIO
-#define SP_MATRIX_PRIO 3
-#endif
-SP_DEV void matrix_phase_begin() { __builtin_amdgcn_s_setprio(SP_MATRIX_PRIO); }
+SP_DEV void matrix_phase_begin() { __builtin_amdgcn_s_setprio(3); }
 SP_DEV void matrix_phase_end() { __builtin_amdgcn_s_setprio(0); }
 
 // End of a phase of the two-group schedules: nothing may be scheduled across the barrier.

@@ -33,9 +33,32 @@ def rel_l2(x, ref):
 
 
 def max_abs(x, ref):
-    both_ninf = np.isneginf(x) & np.isneginf(ref)
-    d = np.where(both_ninf, 0.0, np.abs(x - ref))
-    return float(np.nanmax(d)) if d.size else 0.0
+    """Largest |x - ref| over the finite entries, after checking that x is finite exactly where ref is and
+    equal to it where ref is not (-inf for rows without a visible key).  A NaN anywhere in x fails here:
+    it is never dropped from the maximum."""
+    x, ref = np.asarray(x, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    assert x.shape == ref.shape, (x.shape, ref.shape)
+    fin_x, fin_r = np.isfinite(x), np.isfinite(ref)
+    assert np.array_equal(fin_x, fin_r), "%d entries are finite on one side only (NaN/inf in the result?)" % int((fin_x != fin_r).sum())
+    assert np.array_equal(x[~fin_r], ref[~fin_r]), "non-finite entries differ"
+    d = np.abs(x[fin_r] - ref[fin_r])
+    return float(d.max()) if d.size else 0.0
+
+
+def out_err(o, o_ref, bf16_out):
+    """Forward output error under the stated bound.  A bf16 result is at best half an ulp from the exact value,
+    which passes 1e-2 once |out| >= 4 (rows with a handful of visible keys): such elements are held to half a
+    bf16 ulp at their magnitude plus 2e-3 and counted; all others (every element of a float32 result) to the
+    1e-2 bound.  Returns (largest error among the elements under the 1e-2 rule, count of the others)."""
+    o, o_ref = np.asarray(o, dtype=np.float64), np.asarray(o_ref, dtype=np.float64)
+    assert np.isfinite(o).all(), "non-finite forward output"
+    err = np.abs(o - o_ref)
+    big = (np.abs(o_ref) >= 4.0) if bf16_out else np.zeros(o_ref.shape, dtype=bool)
+    if big.any():
+        half_ulp = 2.0 ** (np.floor(np.log2(np.abs(o_ref[big]))) - 8)
+        assert np.all(err[big] <= half_ulp + 2e-3), "bf16 output off by more than half an ulp + 2e-3 where |out| >= 4"
+    small = err[~big]
+    return (float(small.max()) if small.size else 0.0), int(big.sum())
 
 
 # tolerances of the parity bar (bf16-rounded inputs, fp64 oracle)

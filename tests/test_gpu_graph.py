@@ -1,7 +1,11 @@
 """The hot path under HIP graph capture: the library allocates nothing and synchronises nothing, so one forward
 and one backward call (six kernels) can be captured once and replayed.  Every replay is checked against the eager
-result on fresh inputs, with eager work and synchronisations between the replays."""
+result on fresh inputs, with eager work and synchronisations between the replays.  The second test does the same
+in a process of its own whose FIRST use of the library is the capture, after slimpipe_attn_init()."""
 import math
+import os
+import subprocess
+import sys
 
 import pytest
 
@@ -12,6 +16,20 @@ pytestmark = pytest.mark.gpu
 
 
 def test_forward_backward_replayed_from_a_graph():
+    capture_and_replay(eager_warmup=True)
+
+
+def test_capture_is_the_first_use_after_init():
+    """A fresh process: slimpipe_attn_init(), then the capture, with no eager launch before it."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = ("import sys; sys.path.insert(0, %r); sys.path.insert(0, %r); import test_gpu_graph as t; "
+            "t.capture_and_replay(eager_warmup=False); print('child ok', flush=True)") % (root, os.path.join(root, "tests"))
+    r = subprocess.run([sys.executable, "-u", "-c", code], capture_output=True, text=True, timeout=300)
+    say("child process: rc %d\n%s%s" % (r.returncode, r.stdout[-2000:], r.stderr[-2000:]))
+    assert r.returncode == 0 and "child ok" in r.stdout
+
+
+def capture_and_replay(eager_warmup):
     import torch
     import paper_2504_14519_amd as sp
     B, s, N, Hq, Hkv, D = 1, 512, 2048, 4, 1, 128
@@ -35,9 +53,13 @@ def test_forward_backward_replayed_from_a_graph():
         sp.slimpipe_attn_bwd(q, k, v, out, do, lse, q_off, 0, N, dk, dv, True, scale, dq=dq, dq_dtype=sp.F32,
                              dkv_accumulate=False, workspace=ws)
 
-    say("graph: eager warm-up")
-    step()                      # first use of every kernel happens outside the capture
-    torch.cuda.synchronize()
+    if eager_warmup:
+        say("graph: eager warm-up")
+        step()
+        torch.cuda.synchronize()
+    else:
+        say("graph: slimpipe_attn_init(), no eager launch")
+        sp.slimpipe_attn_init()
     say("graph: capture")
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):

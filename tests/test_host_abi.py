@@ -16,15 +16,21 @@ def sp():
 
 
 def declared_functions():
-    src = open(os.path.join(ROOT, "include", "slimpipe_attn.h")).read()
-    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(slimpipe_attn_[a-z0-9_]+)\s*\(", src)))
+    """Every function declared in any header under include/."""
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for f in sorted(os.listdir(inc)):
+        if f.endswith(".h"):
+            src = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, f)).read(), flags=re.S)
+            names |= set(re.findall(r"\b(slimpipe_attn_[a-z0-9_]+)\s*\(", src))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol(sp):
     names = declared_functions()
     assert {"slimpipe_attn_fwd", "slimpipe_attn_bwd", "slimpipe_attn_merge", "slimpipe_attn_finalize_bf16",
-            "slimpipe_attn_workspace_bytes", "slimpipe_attn_validate", "slimpipe_attn_strerror"} <= set(names)
+            "slimpipe_attn_workspace_bytes", "slimpipe_attn_validate", "slimpipe_attn_strerror", "slimpipe_attn_init",
+            "slimpipe_attn_profile_read", "slimpipe_attn_mfma_rate"} <= set(names)
     L = ctypes.CDLL(sp.library_path())
     for n in names:
         assert hasattr(L, n), n
