@@ -51,7 +51,8 @@ typedef enum slimpipe_status {
   SLIMPIPE_EINVAL_STRIDE = -4,    /* a stride is not a positive multiple of 8 elements             */
   SLIMPIPE_EINVAL_ALIGN = -5,     /* a pointer is not 16-byte aligned                              */
   SLIMPIPE_EWORKSPACE = -6,       /* workspace missing or smaller than slimpipe_attn_workspace_bytes */
-  SLIMPIPE_ELAUNCH = -7           /* the HIP runtime refused a launch                              */
+  SLIMPIPE_ELAUNCH = -7,          /* the HIP runtime refused a launch                              */
+  SLIMPIPE_ETOOLARGE = -8         /* slimpipe_attn_bwd_noalloc: the call needs more than its fixed scratch */
 } slimpipe_status;
 
 enum { SLIMPIPE_BF16 = 0, SLIMPIPE_F32 = 1 };
@@ -133,6 +134,26 @@ int slimpipe_attn_bwd(const slimpipe_attn_params* p,
                       void* dq, int32_t dq_dtype, int32_t dq_accumulate,
                       float* dk_acc, float* dv_acc, int32_t dkv_accumulate,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* slimpipe_attn_bwd for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and kernels as
+ * slimpipe_attn_bwd given a workspace of the minimum size (the dk/dv query stream is not split, dq is not cut
+ * into key ranges), but the two row-statistic arrays the kernels exchange (delta and lse in log2 units, one float
+ * each per (batch, q head, row)) live in a fixed 4 MiB array in device memory that belongs to the library, one
+ * copy per GPU, held until the process ends.  The call allocates nothing (no hipMalloc / hipFree, no events) and
+ * does not synchronise.
+ *   limit : batch * n_q_heads * s_q <= slimpipe_attn_noalloc_max_rows() = 524288, each array rounded up to 256
+ *           bytes; beyond that SLIMPIPE_ETOOLARGE is returned and nothing is launched.
+ *   The array keeps the last call's contents; every call overwrites the entries it reads (nothing has to start at
+ *   zero).  All calls on one GPU share it: two calls whose kernels may overlap on one GPU (different streams, or
+ *   host threads) race - serialise them, or use slimpipe_attn_bwd with a workspace each.  Graph capture:
+ *   call slimpipe_attn_init() before the capture begins. */
+int slimpipe_attn_bwd_noalloc(const slimpipe_attn_params* p,
+                              const void* q_slice, const void* k_prefix, const void* v_prefix,
+                              const void* out, const void* d_out, const float* lse,
+                              void* dq, int32_t dq_dtype, int32_t dq_accumulate,
+                              float* dk_acc, float* dv_acc, int32_t dkv_accumulate, void* hip_stream);
+int slimpipe_attn_noalloc_max_rows(void);
 
 /* Online-softmax merge of n_parts (1..16) partial results over disjoint key sets (Sec. 4.2.2):
  *   lse = ln sum_r exp(lse_r),  out = sum_r exp(lse_r - lse) * out_r   (weight 0 when lse_r = -inf).

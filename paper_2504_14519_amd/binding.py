@@ -58,6 +58,10 @@ def _load():
     L.slimpipe_attn_fwd.restype = ctypes.c_int
     L.slimpipe_attn_bwd.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp, ctypes.c_size_t, vp]
     L.slimpipe_attn_bwd.restype = ctypes.c_int
+    L.slimpipe_attn_bwd_noalloc.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp]
+    L.slimpipe_attn_bwd_noalloc.restype = ctypes.c_int
+    L.slimpipe_attn_noalloc_max_rows.argtypes = []
+    L.slimpipe_attn_noalloc_max_rows.restype = ctypes.c_int
     pp = ctypes.POINTER(vp)
     L.slimpipe_attn_fwd_chunked.argtypes = [P, vp, pp, pp, i32, i64, vp, vp, vp, ctypes.c_size_t, vp]
     L.slimpipe_attn_fwd_chunked.restype = ctypes.c_int
@@ -172,6 +176,23 @@ def slimpipe_attn_bwd(q_slice, k_prefix, v_prefix, out, d_out, lse, q_offset, kv
                                  1 if dq_accumulate else 0, dk_acc.data_ptr(), dv_acc.data_ptr(),
                                  1 if dkv_accumulate else 0, workspace.data_ptr(), workspace.numel(), _stream()),
            "slimpipe_attn_bwd")
+    return dq
+
+
+def slimpipe_attn_bwd_noalloc(q_slice, k_prefix, v_prefix, out, d_out, lse, q_offset, kv_begin, kv_end, dq, dk_acc, dv_acc,
+                              causal=True, scale=None, dq_accumulate=False, dkv_accumulate=True):
+    """slimpipe_attn_bwd without a workspace and without any allocation (the binding allocates nothing either: dq is
+    the caller's, float32 or bf16 by its dtype).  -> the status code's check; results in dq, dk_acc, dv_acc."""
+    import torch
+    if not (_same_strides(dq, q_slice) and _same_strides(dk_acc, k_prefix) and _same_strides(dv_acc, k_prefix)):
+        raise SlimpipeError("dq must have the strides of q; dk_acc/dv_acc those of k")
+    p = make_params(q_slice, k_prefix, out, q_offset, kv_begin, kv_end, causal, scale)
+    p.do_stride_b, p.do_stride_s, p.do_stride_h = d_out.stride(0), d_out.stride(1), d_out.stride(2)
+    _check(lib.slimpipe_attn_bwd_noalloc(ctypes.byref(p), q_slice.data_ptr(), k_prefix.data_ptr(), v_prefix.data_ptr(),
+                                         out.data_ptr(), d_out.data_ptr(), lse.data_ptr(), dq.data_ptr(),
+                                         F32 if dq.dtype == torch.float32 else BF16, 1 if dq_accumulate else 0,
+                                         dk_acc.data_ptr(), dv_acc.data_ptr(), 1 if dkv_accumulate else 0, _stream()),
+           "slimpipe_attn_bwd_noalloc")
     return dq
 
 

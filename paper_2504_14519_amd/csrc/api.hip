@@ -12,6 +12,13 @@
 
 using namespace slimpipe;
 
+// Fixed device memory of the entry point that allocates nothing (slimpipe_attn_bwd_noalloc): the backward's row
+// statistics live here instead of in a caller's workspace.  Every GPU the library runs on holds its own copy
+// until the process ends.  Host code never uses this name as an address: it asks the runtime for the device
+// address once per device (ensure_device_ready) and passes that pointer to the kernels.
+constexpr size_t kScratchBytes = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
 
 bool stride_ok(int64_t s) { return s > 0 && (s % 8) == 0; }
@@ -31,19 +38,23 @@ constexpr int kMaxDevices = 64;
 struct DeviceState {
   std::once_flag once;
   hipError_t status = hipSuccess;
+  void* scratch = nullptr;       // this device's copy of `scratch` below (its address differs from device to device)
 };
 DeviceState g_device[kMaxDevices];
 std::atomic<int> g_compute_units[kMaxDevices];
 
 // Makes the current device ready for launches: SLIMPIPE_OK, or SLIMPIPE_ELAUNCH when the runtime refuses.
-int ensure_device_ready() {
+int ensure_device_ready(void** scratch_ptr = nullptr) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SLIMPIPE_ELAUNCH;
   DeviceState& d = g_device[dev];
   std::call_once(d.once, [&d] {
     d.status = opt_in_fwd_kernels();
     if (d.status == hipSuccess) d.status = opt_in_bwd_kernels();
+    if (d.status == hipSuccess) d.status = hipGetSymbolAddress(&d.scratch, HIP_SYMBOL(scratch));
+    if (d.status == hipSuccess && d.scratch == nullptr) d.status = hipErrorInvalidSymbol;
   });
+  if (scratch_ptr) *scratch_ptr = d.scratch;
   return d.status == hipSuccess ? SLIMPIPE_OK : SLIMPIPE_ELAUNCH;
 }
 
@@ -189,8 +200,8 @@ hipEvent_t prof_event() {                    // (caller holds g_prof_mutex)
 }
 
 template <class F>
-hipError_t timed(int kind, hipStream_t st, F&& launch) {
-  if (!g_prof_on.load(std::memory_order_relaxed)) return launch();
+hipError_t timed(int kind, hipStream_t st, F&& launch, bool allow = true) {
+  if (!allow || !g_prof_on.load(std::memory_order_relaxed)) return launch();
   std::lock_guard<std::mutex> lock(g_prof_mutex);
   ProfRecord r{kind, prof_event(), prof_event()};
   if (!r.start || !r.stop) return launch();
@@ -398,7 +409,7 @@ static int bwd_impl(const slimpipe_attn_params* p, const void* q_slice, const vo
                     const void* const* v_chunks, int32_t n_chunks, int64_t chunk_len, const void* out,
                     const void* d_out, const float* lse, void* dq, int32_t dq_dtype, int32_t dq_accumulate,
                     float* const* dk_chunks, float* const* dv_chunks, int32_t dkv_accumulate, void* workspace,
-                    size_t workspace_bytes, void* hip_stream) {
+                    size_t workspace_bytes, void* hip_stream, bool events = true) {
   int rc = slimpipe_attn_validate(p, 1);
   if (rc != SLIMPIPE_OK) return rc;
   if (!q_slice || !out || !d_out || !lse || !dq || !k_chunks || !v_chunks || !dk_chunks || !dv_chunks) return SLIMPIPE_EINVAL_NULL;
@@ -467,14 +478,14 @@ static int bwd_impl(const slimpipe_attn_params* p, const void* q_slice, const vo
   a.do_stride_b = p->do_stride_b; a.do_stride_s = p->do_stride_s; a.do_stride_h = p->do_stride_h;
   if (ensure_device_ready() != SLIMPIPE_OK) return SLIMPIPE_ELAUNCH;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  if (timed(SLIMPIPE_KERNEL_DELTA, st, [&] { return launch_delta(a, p->batch, p->head_dim, st); }) != hipSuccess) return SLIMPIPE_ELAUNCH;
-  if (timed(SLIMPIPE_KERNEL_DQ, st, [&] { return launch_bwd_dq(a, p->batch, p->head_dim, st); }) != hipSuccess) return SLIMPIPE_ELAUNCH;
+  if (timed(SLIMPIPE_KERNEL_DELTA, st, [&] { return launch_delta(a, p->batch, p->head_dim, st); }, events) != hipSuccess) return SLIMPIPE_ELAUNCH;
+  if (timed(SLIMPIPE_KERNEL_DQ, st, [&] { return launch_bwd_dq(a, p->batch, p->head_dim, st); }, events) != hipSuccess) return SLIMPIPE_ELAUNCH;
   if (dq_ranges > 1 &&
-      timed(SLIMPIPE_KERNEL_DQ_REDUCE, st, [&] { return launch_dq_reduce(a, p->batch, p->head_dim, st); }) != hipSuccess)
+      timed(SLIMPIPE_KERNEL_DQ_REDUCE, st, [&] { return launch_dq_reduce(a, p->batch, p->head_dim, st); }, events) != hipSuccess)
     return SLIMPIPE_ELAUNCH;
-  if (timed(SLIMPIPE_KERNEL_DKDV, st, [&] { return launch_bwd_dkdv(a, p->batch, p->head_dim, st); }) != hipSuccess) return SLIMPIPE_ELAUNCH;
+  if (timed(SLIMPIPE_KERNEL_DKDV, st, [&] { return launch_bwd_dkdv(a, p->batch, p->head_dim, st); }, events) != hipSuccess) return SLIMPIPE_ELAUNCH;
   if (split > 1 &&
-      timed(SLIMPIPE_KERNEL_DKDV_REDUCE, st, [&] { return launch_dkdv_reduce(a, p->batch, p->head_dim, st); }) != hipSuccess)
+      timed(SLIMPIPE_KERNEL_DKDV_REDUCE, st, [&] { return launch_dkdv_reduce(a, p->batch, p->head_dim, st); }, events) != hipSuccess)
     return SLIMPIPE_ELAUNCH;
   return SLIMPIPE_OK;
 }
@@ -487,6 +498,24 @@ int slimpipe_attn_bwd(const slimpipe_attn_params* p, const void* q_slice, const 
   return bwd_impl(p, q_slice, &k_prefix, &v_prefix, 1, p->kv_capacity > 0 ? p->kv_capacity : 1, out, d_out, lse, dq, dq_dtype,
                   dq_accumulate, &dk_acc, &dv_acc, dkv_accumulate, workspace, workspace_bytes, hip_stream);
 }
+
+int slimpipe_attn_bwd_noalloc(const slimpipe_attn_params* p, const void* q_slice, const void* k_prefix,
+                              const void* v_prefix, const void* out, const void* d_out, const float* lse, void* dq,
+                              int32_t dq_dtype, int32_t dq_accumulate, float* dk_acc, float* dv_acc,
+                              int32_t dkv_accumulate, void* hip_stream) {
+  if (!p) return SLIMPIPE_EINVAL_NULL;
+  int rc = slimpipe_attn_validate(p, 1);
+  if (rc != SLIMPIPE_OK) return rc;
+  if (delta_bytes(p) > kScratchBytes) return SLIMPIPE_ETOOLARGE;
+  void* ws = nullptr;
+  if (ensure_device_ready(&ws) != SLIMPIPE_OK || !ws) return SLIMPIPE_ELAUNCH;
+  // exactly the two statistics arrays: no split of the dk/dv query stream, no key ranges for dq (the plan of
+  // slimpipe_attn_bwd given a workspace of the minimum size), and no event records of the benchmark switch
+  return bwd_impl(p, q_slice, &k_prefix, &v_prefix, 1, p->kv_capacity > 0 ? p->kv_capacity : 1, out, d_out, lse, dq, dq_dtype,
+                  dq_accumulate, &dk_acc, &dv_acc, dkv_accumulate, ws, delta_bytes(p), hip_stream, false);
+}
+
+int slimpipe_attn_noalloc_max_rows(void) { return (int)(kScratchBytes / (2 * sizeof(float))); }
 
 int slimpipe_attn_bwd_chunked(const slimpipe_attn_params* p, const void* q_slice, const void* const* k_chunks,
                               const void* const* v_chunks, int32_t n_chunks, int64_t chunk_len, const void* out,
@@ -563,6 +592,7 @@ const char* slimpipe_attn_strerror(int code) {
     case SLIMPIPE_EINVAL_ALIGN: return "pointer not 16-byte aligned";
     case SLIMPIPE_EWORKSPACE: return "workspace missing or too small";
     case SLIMPIPE_ELAUNCH: return "HIP launch failed";
+    case SLIMPIPE_ETOOLARGE: return "batch * heads * rows exceeds the fixed scratch of slimpipe_attn_bwd_noalloc";
     default: return "unknown slimpipe status";
   }
 }
