@@ -6,7 +6,12 @@ in order against its cached K/V prefix, then backward of every slice in reverse 
 accumulated in fp32 (the call order of the slice-wise schedule, paper Sec. 4.1.2).  Inputs are
 resident in HBM before the timed region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama70b_tp8_share] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama70b_tp8_share] [--slices n] [--no-cpu-baseline]
+
+The headline (`value`, `ms_per_step`) is timed with nothing but the library's kernels on the stream.  The per-kernel
+breakdown behind `roofline` comes from a SECOND pass of the same steps in which every kernel is bracketed by HIP
+events on the stream it runs on.  `cpu_baseline` times the fp64 oracle on a sample of the same seeded tensors, and
+`parity` compares the library's result on that same sample with what the oracle returned there (outside any timing).
 """
 import argparse
 import json
@@ -43,6 +48,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="llama70b_tp8_share")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--slices", type=int, default=None,
+                    help="cut the workload's sequence into this many slices instead of its own count (slice-length sweep)")
     ap.add_argument("--chunked", action="store_true",
                     help="K/V and the dK/dV accumulators as one allocation per slice (the paper's chunked cache) instead of one buffer")
     ap.add_argument("--no-fwd-ranges", action="store_true",
@@ -50,7 +57,12 @@ def main():
     ap.add_argument("--schedule-sim", default=None, metavar="P,M",
                     help="also time every slice's forward and backward call and feed the times to the slice-wise 1F1B "
                          "schedule simulator with P pipeline devices and M microbatches (adds a 'schedule_sim' object)")
+    ap.add_argument("--probe-dq-atomics", action="store_true",
+                    help="instead of the benchmark: time the float32 atomic adds a fused (scores-once) backward would need "
+                         "for dq, in that kernel's access pattern, alone and under a stream of matrix instructions")
     args = ap.parse_args()
+    if args.probe_dq_atomics:
+        return probe_dq_atomics()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported" % args.gpus,
               file=sys.stderr)
@@ -67,8 +79,12 @@ def main():
     cfg_id = cfg_id[0]
     c = CONFIGS[cfg_id]
     N, n, Hq, Hkv, D = c["N"], c["n"], c["Hq"], c["Hkv"], c["D"]
+    if args.slices:
+        if N % args.slices or (N // args.slices) % 256:
+            sys.exit("--slices must cut the sequence into equal slices of a multiple of 256 rows")
+        n = args.slices
     s = N // n
-    first_slice = n - 8 if c["name"] == "longest" else 0     # the longest config runs its final 8 slices only
+    first_slice = n - n // 8 if c["name"] == "longest" else 0     # the longest config runs its final eighth only
     scale = 1.0 / math.sqrt(D)
     dev = "cuda:0"
 
@@ -164,40 +180,61 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # pass 1, the headline: nothing on the stream but the library's kernels
+    sp.slimpipe_attn_profile_enable(False)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = flops_step / (ms_per_step * 1e-3) / 1e12
+    # pass 2, the breakdown: the same steps with every kernel bracketed by HIP events on its stream
     sp.slimpipe_attn_profile_enable(True)
     sp.slimpipe_attn_profile_read()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    ms_per_step_pass2 = (time.perf_counter() - t0) * 1e3 / args.steps
     prof = sp.slimpipe_attn_profile_read()
     sp.slimpipe_attn_profile_enable(False)
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    value = flops_step / (ms_per_step * 1e-3) / 1e12
 
-    # dominant kernel = the one with the largest share of the timed region
-    alg_flops = {"fwd": 4.0, "dq": 6.0, "dkdv": 8.0}       # x D x Hq x pairs: what each kernel computes
-    kshare = {kk: prof[kk][0] for kk in alg_flops}
+    # Flop per visible pair and q head, in units of D.  "issued": what each kernel computes (S = QK^T and dP = dO V^T are
+    # computed by BOTH backward kernels).  "credited": the 10*D of the backward counted once, the duplicated 4*D split
+    # evenly between dq and dk/dv, so that the credited figures add up to the 14*D of `value`.
+    issued = {"fwd": 4.0, "dq": 6.0, "dkdv": 8.0}
+    credited = {"fwd": 4.0, "dq": 4.0, "dkdv": 6.0}
+    kshare = {kk: prof[kk][0] for kk in issued}
     dom = max(kshare, key=kshare.get)
     dom_ms, dom_n = prof[dom]
-    dom_flops_total = alg_flops[dom] * D * Hq * pairs_total * args.steps
-    achieved = dom_flops_total / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
+    per_d = D * Hq * pairs_total * args.steps
+
+    def rate(flop_units, ms):
+        return flop_units * per_d / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
+
+    achieved = rate(credited[dom], dom_ms)
+    bwd_ms = sum(prof[kk][0] for kk in ("delta", "dq", "dq_reduce", "dkdv", "dkdv_reduce"))
     roofline = {
         "bound": "mfma", "kernel": dom, "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
         "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": stored_traffic(c["name"], dom),
+        "flop_accounting": "credited: %g*D per visible pair and q head for %s (S and dP, which both backward kernels "
+                           "compute, counted once and split between them); the kernel issues %g*D" % (credited[dom], dom, issued[dom]),
+        "achieved_issued": round(rate(issued[dom], dom_ms), 1),
         "launches": int(dom_n), "avg_launch_ms": round(dom_ms / max(1, dom_n), 4),
-        "flops_per_launch_avg": dom_flops_total / max(1, dom_n),
+        "flops_per_launch_avg_credited": credited[dom] * per_d / max(1, dom_n),
         "kernel_ms_per_step": {kk: round(prof[kk][0] / args.steps, 3) for kk in prof},
-        "kernel_tflops": {kk: round(alg_flops[kk] * D * Hq * pairs_total * args.steps / (prof[kk][0] * 1e-3) / 1e12, 1)
-                          for kk in alg_flops if prof[kk][0] > 0},
+        "kernel_tflops_issued": {kk: round(rate(issued[kk], prof[kk][0]), 1) for kk in issued if prof[kk][0] > 0},
+        "kernel_tflops_credited": {kk: round(rate(credited[kk], prof[kk][0]), 1) for kk in issued if prof[kk][0] > 0},
+        "backward_tflops_10D": round(rate(10.0, bwd_ms), 1),
+        "ms_per_step_with_event_bracketing": round(ms_per_step_pass2, 3),
     }
 
     # what a pure stream of the same MFMA instruction sustains on this GPU (after the timed region): with
     # random operands the chip is power limited, which is the regime the attention kernels run in
     roofline["mfma_stream_tflops"] = {"constant_operands": round(sp.slimpipe_attn_mfma_rate(False), 1),
                                       "random_operands": round(sp.slimpipe_attn_mfma_rate(True), 1)}
-    roofline["frac_of_mfma_stream_random"] = round(achieved / max(roofline["mfma_stream_tflops"]["random_operands"], 1e-9), 4)
+    roofline["issued_frac_of_mfma_stream_random"] = round(roofline["achieved_issued"] / max(roofline["mfma_stream_tflops"]["random_operands"], 1e-9), 4)
 
     out = {
         "metric": "sliced causal attn fwd+bwd TFLOP/s and % of MI355X bf16 MFMA peak",
@@ -216,8 +253,32 @@ def main():
     if args.schedule_sim:
         out["schedule_sim"] = schedule_sim(args.schedule_sim, n, nrun, slices, step, torch)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg_id, c, s, scale)
+        out["cpu_baseline"], out["parity"] = cpu_baseline_and_parity(sp, torch, q, k if not args.chunked else torch.cat(kc, dim=1),
+                                                                     v if not args.chunked else torch.cat(vc, dim=1), do, c, n, s,
+                                                                     first_slice, scale)
     print(json.dumps(out), flush=True)
+
+
+def probe_dq_atomics():
+    """One JSON line per variant.  Shape: one backward call of the 256K workload's slice 15 (16384 rows, 8 q heads) over
+    256 key tiles (one round of workgroups per head on a 256-CU chip would be 32; 256 x 8 = 2048 workgroups = 8 rounds).
+    Needed rate: a fused backward at R TFLOP/s (10*D = 1280 flop per pair and head) makes R/1280 T pairs/s; with
+    rows_per_step = 32 it adds 4 bytes of dq per pair, with 64 it adds 2."""
+    import paper_2504_14519_amd as sp
+    s_q, heads, key_tiles = 16384, 8, 256
+    for rows in (32, 64):
+        pairs = float(s_q) * 256 * key_tiles * heads
+        bytes_total = pairs * (4.0 if rows == 32 else 2.0)
+        for placement in (0, 1):
+            for rotate in (0, 1):
+                for filler, atomics in ((0, True), (40 * rows // 32, False), (40 * rows // 32, True)):
+                    ms, ok, mism = sp.slimpipe_attn_dq_atomic_probe(s_q, heads, key_tiles, rows, placement, rotate, filler, atomics)
+                    ms, ok, mism = sp.slimpipe_attn_dq_atomic_probe(s_q, heads, key_tiles, rows, placement, rotate, filler, atomics)
+                    print(json.dumps({"probe": "dq_atomics", "rows_per_step": rows, "placement": placement, "rotate": rotate,
+                                      "filler_mfma_per_step": filler, "atomics": atomics, "ms": round(ms, 3),
+                                      "atomic_TBps": round(bytes_total / (ms * 1e-3) / 1e12, 3) if atomics else None,
+                                      "equiv_fused_bwd_TFLOPs": round(pairs * 1280.0 / (ms * 1e-3) / 1e12, 1),
+                                      "sum_ok": ok, "wg_not_on_xcd_w_mod_8": mism}), flush=True)
 
 
 def schedule_sim(spec, n, nrun, slices, step, torch):
@@ -270,23 +331,27 @@ def stored_traffic(workload, kernel):
     return None
 
 
-def cpu_baseline(cfg_id, c, s, scale):
-    """The fp64 oracle, as it stands, timed on the host cores on a bounded sample of the workload."""
+def cpu_baseline_and_parity(sp, torch, q, k, v, do, c, n, s, first_slice, scale):
+    """The fp64 oracle, as it stands, timed on the host cores on a bounded sample of the workload's own tensors: the
+    first `rows` rows of one slice (all heads) as a call of their own against their whole prefix.  The same call then
+    runs through the library (outside any timing) and the two results are compared: `parity`."""
     import numpy as np
     from oracle import attn_fwd, attn_bwd
-    from synth_inputs import normal_bf16, bf16_bits_to_f64
     Hq, Hkv, D = c["Hq"], c["Hkv"], c["D"]
-    rows = min(s, 4096)                          # about 10-15 s of host work, a few GB of fp64 scores per head
-    i = min(2, c["n"] - 1)                        # third slice: two cached slices + the diagonal block
+    i = min(first_slice + 2, n - 1)               # third slice that runs: cached slices + the diagonal block
+    j = i - first_slice                            # its index among the query slices held on the device
+    budget = 1.4e8 * 8 / Hq                        # (row, key) pairs per head: 10-20 s of host work on 16 cores
+    rows = int(min(s, 4096, max(256, budget // (i * s + 2048) // 256 * 256)))
     kv_end = i * s + rows
-    rng_cfg = 15                                  # its own seed family: a sample, not the workload tensors
-    q = bf16_bits_to_f64(normal_bf16((1, rows, Hq, D), rng_cfg, "q"))
-    do = bf16_bits_to_f64(normal_bf16((1, rows, Hq, D), rng_cfg, "do"))
-    k = bf16_bits_to_f64(normal_bf16((1, kv_end, Hkv, D), rng_cfg, "k"))
-    v = bf16_bits_to_f64(normal_bf16((1, kv_end, Hkv, D), rng_cfg, "v"))
+    rs = slice(j * s, j * s + rows)
+
+    def f64(t):
+        return t.to(torch.float32).cpu().numpy().astype(np.float64)
+
+    q64, do64, k64, v64 = f64(q[:, rs]), f64(do[:, rs]), f64(k[:, :kv_end]), f64(v[:, :kv_end])
     t0 = time.perf_counter()
-    o, lse = attn_fwd(q, k, v, i * s, 0, kv_end, True, scale)
-    attn_bwd(q, k, v, o, do, lse, i * s, 0, kv_end, True, scale)
+    o_ref, l_ref = attn_fwd(q64, k64, v64, i * s, 0, kv_end, True, scale)
+    dq_ref, dk_ref, dv_ref = attn_bwd(q64, k64, v64, o_ref, do64, l_ref, i * s, 0, kv_end, True, scale)
     dt = time.perf_counter() - t0
     pairs = visible_pairs(rows, i * s, 0, kv_end)
     tf = 14.0 * D * Hq * pairs / dt / 1e12
@@ -295,9 +360,33 @@ def cpu_baseline(cfg_id, c, s, scale):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count()
-    return {"value": round(tf, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-            "sample": "fwd+bwd of the first %d rows of slice %d (all %d q heads) against keys [0,%d), fp64 numpy; %.1f s"
-                      % (rows, i, Hq, kv_end, dt)}
+    sample = ("fwd+bwd of the first %d rows of slice %d (all %d q heads, the workload's own tensors) against keys [0,%d), "
+              "fp64 numpy; %.1f s" % (rows, i, Hq, kv_end, dt))
+    base = {"value": round(tf, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle", "sample": sample}
+
+    # the library on the same call: forward, then backward from ITS OWN out / lse (the whole chain against the oracle's)
+    kk, vv = k[:, :kv_end], v[:, :kv_end]
+    out, lse = sp.slimpipe_attn_fwd(q[:, rs], kk, vv, i * s, 0, kv_end, True, scale)
+    dk = torch.zeros((1, kv_end, Hkv, D), device=q.device, dtype=torch.float32)
+    dv = torch.zeros_like(dk)
+    dq = sp.slimpipe_attn_bwd(q[:, rs], kk, vv, out, do[:, rs], lse, i * s, 0, kv_end, dk, dv, True, scale, dq_dtype=sp.F32,
+                              dkv_accumulate=False)
+    torch.cuda.synchronize()
+
+    def rel(x, ref):
+        x = x.cpu().numpy().astype(np.float64)
+        return float(np.linalg.norm(x - ref) / np.linalg.norm(ref))
+
+    og, lg = f64(out), lse.cpu().numpy().astype(np.float64)
+    finite = bool(np.isfinite(og).all() and np.isfinite(lg).all() and torch.isfinite(dq).all() and torch.isfinite(dk).all()
+                  and torch.isfinite(dv).all())
+    parity = {"sample": "the cpu_baseline sample: GPU forward -> GPU backward against oracle forward -> oracle backward",
+              "out_max_abs": float(np.abs(og - o_ref).max()), "lse_max_abs": float(np.abs(lg - l_ref).max()),
+              "dq_rel_l2": rel(dq, dq_ref), "dk_rel_l2": rel(dk, dk_ref), "dv_rel_l2": rel(dv, dv_ref), "all_finite": finite,
+              "tolerances": {"out_max_abs": 1e-2, "lse_max_abs": 1e-3, "grad_rel_l2": 2e-2}}
+    parity["within_tolerance"] = bool(finite and parity["out_max_abs"] <= 1e-2 and parity["lse_max_abs"] <= 1e-3 and
+                                      max(parity["dq_rel_l2"], parity["dk_rel_l2"], parity["dv_rel_l2"]) <= 2e-2)
+    return base, parity
 
 
 if __name__ == "__main__":

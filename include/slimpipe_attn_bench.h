@@ -31,6 +31,20 @@ int slimpipe_attn_profile_read(double total_ms[SLIMPIPE_KERNEL_KINDS], int64_t l
  * sink: device pointer to at least one float (never written in practice). */
 int slimpipe_attn_mfma_rate(int random_operands, float* sink, double* tflops, void* hip_stream);
 
+/* What float32 atomic adds into dq would cost a backward kernel that computes the scores once (key-stationary, dK/dV
+ * in registers, dQ added into memory).  Launches key_tiles * heads workgroups of 8 waves; each walks the s_q /
+ * rows_per_step query tiles of one head and per tile adds 1.0f to a rows_per_step x 128 block of dq
+ * ([s_q, heads, 128] float32, device, zero before the call) as eight 32 x 32 MFMA C tiles with head_dim along the
+ * lanes (rows_per_step = 32: two waves per tile add to the same 32 rows; 64: each wave its own 32 rows), with
+ * filler_mfma (multiple of 4) matrix instructions per wave and step in between, and with_atomics = 0 leaving the
+ * adds out.  placement 0: consecutive workgroups share a head; 1: workgroup w takes head w % heads and counts in
+ * *xcc_mismatch (device, zero before the call) the workgroups whose XCD differs from w % 8.  rotate != 0 shifts the
+ * start tile by the workgroup's key tile.  Afterwards every element of dq holds key_tiles * (64 / rows_per_step).
+ * Waits for the kernel; *ms = its duration. */
+int slimpipe_attn_dq_atomic_probe(float* dq, int32_t s_q, int32_t heads, int32_t key_tiles, int32_t rows_per_step,
+                                  int32_t placement, int32_t rotate, int32_t filler_mfma, int32_t with_atomics,
+                                  uint32_t* xcc_mismatch, double* ms, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -45,6 +45,10 @@ def _load():
         except Exception as e:
             raise ImportError("libslimpipe_attn.so is not built and building it failed (%s): run "
                               "`python paper_2504_14519_amd/build.py`" % e)
+    # torch first: the tensors and streams handed to the library come from torch's HIP runtime, so that runtime has
+    # to be the one already in the process when the library's dependency on libamdhip64 is resolved (loaded the other
+    # way round, the library can end up on a second runtime instance that sees no device)
+    import torch  # noqa: F401
     L = ctypes.CDLL(_LIB_PATH)
     P = ctypes.POINTER(AttnParams)
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
@@ -75,6 +79,8 @@ def _load():
     L.slimpipe_attn_finalize_bf16.restype = ctypes.c_int
     L.slimpipe_attn_mfma_rate.argtypes = [ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double), vp]
     L.slimpipe_attn_mfma_rate.restype = ctypes.c_int
+    L.slimpipe_attn_dq_atomic_probe.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+    L.slimpipe_attn_dq_atomic_probe.restype = ctypes.c_int
     L.slimpipe_attn_profile_enable.argtypes = [ctypes.c_int]
     L.slimpipe_attn_profile_enable.restype = ctypes.c_int
     L.slimpipe_attn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
@@ -327,6 +333,21 @@ def slimpipe_attn_mfma_rate(random_operands):
     tf = ctypes.c_double(0.0)
     _check(lib.slimpipe_attn_mfma_rate(1 if random_operands else 0, sink.data_ptr(), ctypes.byref(tf), _stream()), "mfma_rate")
     return tf.value
+
+
+def slimpipe_attn_dq_atomic_probe(s_q, heads, key_tiles, rows_per_step, placement, rotate, filler_mfma, with_atomics):
+    """-> (ms, every element of dq holds the expected count, workgroups not on XCD w % 8 [placement 1 only])."""
+    import torch
+    dq = torch.zeros((s_q, heads, 128), device="cuda", dtype=torch.float32)
+    mism = torch.zeros(1, device="cuda", dtype=torch.int32)
+    ms = ctypes.c_double(0.0)
+    torch.cuda.synchronize()
+    rc = lib.slimpipe_attn_dq_atomic_probe(dq.data_ptr(), s_q, heads, key_tiles, rows_per_step, placement, rotate, filler_mfma,
+                                           1 if with_atomics else 0, mism.data_ptr(), ctypes.byref(ms), _stream())
+    _check(rc, "dq_atomic_probe (step/HIP error %s)" % ms.value)
+    want = float(key_tiles * (64 // rows_per_step)) if with_atomics else 0.0
+    ok = bool((dq == want).all())
+    return ms.value, ok, int(mism.item())
 
 
 def slimpipe_attn_profile_enable(enable):

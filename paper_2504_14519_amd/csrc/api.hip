@@ -582,6 +582,29 @@ int slimpipe_attn_mfma_rate(int random_operands, float* sink, double* tflops, vo
   return rc;
 }
 
+int slimpipe_attn_dq_atomic_probe(float* dq, int32_t s_q, int32_t heads, int32_t key_tiles, int32_t rows_per_step,
+                                  int32_t placement, int32_t rotate, int32_t filler_mfma, int32_t with_atomics,
+                                  uint32_t* xcc_mismatch, double* ms, void* hip_stream) {
+  if (!dq || !xcc_mismatch || !ms) return SLIMPIPE_EINVAL_NULL;
+  if (s_q <= 0 || heads <= 0 || key_tiles <= 0 || (rows_per_step != 32 && rows_per_step != 64) || s_q % rows_per_step != 0 ||
+      filler_mfma < 0 || filler_mfma % 4 != 0 || (int64_t)key_tiles * heads > 1 << 20)
+    return SLIMPIPE_EINVAL_SHAPE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  // on failure *ms = -(1000 * step + HIP error code), so that a benchmark log names the call that failed
+  float t = 0.f;
+  int step = 0;
+  hipError_t e = hipSuccess;
+  auto run = [&](hipError_t r) { ++step; if (e == hipSuccess && r != hipSuccess) { e = r; return false; } return e == hipSuccess; };
+  run(hipEventCreate(&e0)) && run(hipEventCreate(&e1)) && run(hipEventRecord(e0, st)) &&
+      run(launch_dq_atomic_probe(dq, s_q, heads, key_tiles, rows_per_step, placement, rotate, filler_mfma, with_atomics, xcc_mismatch, st)) &&
+      run(hipEventRecord(e1, st)) && run(hipEventSynchronize(e1)) && run(hipEventElapsedTime(&t, e0, e1));
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  *ms = e == hipSuccess ? (double)t : -(1000.0 * step + (double)(int)e);
+  return e == hipSuccess ? SLIMPIPE_OK : SLIMPIPE_ELAUNCH;
+}
+
 const char* slimpipe_attn_strerror(int code) {
   switch (code) {
     case SLIMPIPE_OK: return "ok";

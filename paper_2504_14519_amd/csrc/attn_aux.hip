@@ -134,4 +134,67 @@ hipError_t launch_mfma_rate(int random, int iters, int workgroups, float* sink, 
   return hipGetLastError();
 }
 
+// ---- measurement aid: what float32 atomic adds cost in the access pattern of a fused backward ----
+// A backward kernel that computes S and dP once would be key-stationary (dK/dV stay in registers, summed in a
+// fixed order) and would have to ADD its dQ contributions into memory: per step a workgroup of 8 waves owning
+// 256 keys of one head holds a 32 x 128 (rows_per_step = 32: two partial sums over 128 keys each) or 64 x 128
+// (rows_per_step = 64: one sum over 256 keys) block of dQ as eight 32 x 32 MFMA C tiles, lane = head_dim column,
+// register = query row, so that one atomic instruction of a wave covers two full 128-byte lines.  This kernel
+// issues exactly those atomic adds for `key_tiles` x `heads` workgroups that each walk every query tile of a
+// slice of `s_q` rows, optionally with `filler_mfma` matrix instructions per wave and step standing in for the
+// five GEMMs (40 per 32 rows), and nothing else.
+//   placement 0: consecutive workgroups share a head (every XCD adds into every head's dQ)
+//   placement 1: workgroup w works on head w % heads (with 8 heads and round-robin dispatch: one head per XCD)
+//   rotate     : start tile of workgroup w shifted by w's key tile (spreads the workgroups over the rows)
+__global__ __launch_bounds__(512) void dq_atomic_probe_kernel(float* dq, int s_q, int heads, int key_tiles, int rows_per_step,
+                                                              int placement, int rotate, int filler_mfma, int with_atomics,
+                                                              unsigned* xcc_mismatch) {
+  const int w = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5, col = lane & 31;
+  const int h = placement ? w % heads : w / key_tiles;
+  const int kt = placement ? w / heads : w % key_tiles;
+  if (placement && threadIdx.x == 0) {
+    // XCC_ID (hardware register 20, bits 3:0): which XCD this workgroup runs on
+    const unsigned xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));
+    if ((int)xcc != (w % 8)) atomicAdd(xcc_mismatch, 1u);
+  }
+  const int steps = s_q / rows_per_step;
+  const int db = wave & 3, half = wave >> 2;
+  const int row_in_step = rows_per_step == 64 ? 32 * half : 0;
+  bf16x8 a, b;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    unsigned ha = (threadIdx.x * 16u + j) * 2654435761u, hb = (threadIdx.x * 16u + 8u + j) * 2246822519u;
+    a[j] = __builtin_bit_cast(bf16_t, (unsigned short)(((0x77u + (ha & 7u)) << 7) | ((ha >> 8) & 0x7fu) | ((ha >> 16) & 0x8000u)));
+    b[j] = __builtin_bit_cast(bf16_t, (unsigned short)(((0x77u + (hb & 7u)) << 7) | ((hb >> 8) & 0x7fu) | ((hb >> 16) & 0x8000u)));
+  }
+  f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+  const int t0 = rotate ? (kt * 7) % steps : 0;
+  for (int i = 0; i < steps; ++i) {
+    int t = t0 + i;
+    if (t >= steps) t -= steps;
+    for (int m = 0; m < filler_mfma; m += 4) {
+      c0 = mfma32(a, b, c0); c1 = mfma32(b, a, c1); c2 = mfma32(a, a, c2); c3 = mfma32(b, b, c3);
+    }
+    if (with_atomics) {
+      float* base = dq + ((int64_t)(t * rows_per_step + row_in_step) * heads + h) * 128 + 32 * db + col;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = 8 * (r >> 2) + 4 * g + (r & 3);
+        unsafeAtomicAdd(base + (int64_t)row * heads * 128, 1.0f);
+      }
+    }
+  }
+  float tsum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) tsum += c0[i] + c1[i] + c2[i] + c3[i];
+  if (tsum == 12345.678f) dq[0] = tsum;          // keeps the filler alive; practically never true
+}
+
+hipError_t launch_dq_atomic_probe(float* dq, int s_q, int heads, int key_tiles, int rows_per_step, int placement, int rotate,
+                                  int filler_mfma, int with_atomics, unsigned* xcc_mismatch, hipStream_t st) {
+  hipLaunchKernelGGL(dq_atomic_probe_kernel, dim3((unsigned)(key_tiles * heads)), dim3(512), 0, st, dq, s_q, heads, key_tiles,
+                     rows_per_step, placement, rotate, filler_mfma, with_atomics, xcc_mismatch);
+  return hipGetLastError();
+}
+
 }  // namespace slimpipe
