@@ -54,9 +54,10 @@ def main():
                     help="K/V and the dK/dV accumulators as one allocation per slice (the paper's chunked cache) instead of one buffer")
     ap.add_argument("--no-fwd-ranges", action="store_true",
                     help="never cut a forward call into key ranges (for comparison on workloads with short slices)")
-    ap.add_argument("--schedule-sim", default=None, metavar="P,M",
+    ap.add_argument("--schedule-sim", default=None, metavar="P,M[,V]",
                     help="also time every slice's forward and backward call and feed the times to the slice-wise 1F1B "
-                         "schedule simulator with P pipeline devices and M microbatches (adds a 'schedule_sim' object)")
+                         "schedule simulator with P pipeline devices, M microbatches and V stages per device (default 1; "
+                         "adds a 'schedule_sim' object)")
     ap.add_argument("--probe-dq-atomics", action="store_true",
                     help="instead of the benchmark: time the float32 atomic adds a fused (scores-once) backward would need "
                          "for dq, in that kernel's access pattern, alone and under a stream of matrix instructions")
@@ -285,8 +286,9 @@ def schedule_sim(spec, n, nrun, slices, step, torch):
     """Per-slice attention times of this GPU (events on the stream the calls go to, after each slice's forward
     call and each slice's backward call, inside one more pass of the step) -> what the paper's schedule makes of
     them: bubble fraction without the context exchange and with it, accumulated activation (Sec. 4.1.3, 4.2)."""
-    from paper_2504_14519_amd.schedule_sim import simulate, simulate_lockstep, accumulated_fraction
-    p_dev, m_mb = (int(x) for x in spec.split(","))
+    from paper_2504_14519_amd.schedule_sim import simulate_interleaved, simulate_lockstep, accumulated_fraction_interleaved
+    parts = [int(x) for x in spec.split(",")]
+    p_dev, m_mb, v_st = parts[0], parts[1], (parts[2] if len(parts) > 2 else 1)
     if nrun != n or slices[0] != 0:
         return {"error": "needs a workload that runs every slice"}
     marks = []
@@ -302,18 +304,19 @@ def schedule_sim(spec, n, nrun, slices, step, torch):
     t = {"F": [0.0] * n, "B": [0.0] * n}
     for (_, _, e0), (kind, j, e1) in zip(marks[:-1], marks[1:]):
         t[kind][j] = e0.elapsed_time(e1)
-    res = {"p": p_dev, "m": m_mb, "n": n, "fwd_ms_by_slice": [round(x, 3) for x in t["F"]],
+    res = {"p": p_dev, "m": m_mb, "n": n, "v": v_st, "fwd_ms_by_slice": [round(x, 3) for x in t["F"]],
            "bwd_ms_by_slice": [round(x, 3) for x in t["B"]],
-           "accumulated_activation_fraction_of_Ma": round(accumulated_fraction(p_dev, n, max(m_mb, 2 * p_dev)), 4),
-           "warmup_cooldown_bound": round((p_dev - 1.0) / (n * m_mb), 5), "bubble_fraction": {}}
+           "accumulated_activation_fraction_of_Ma": round(accumulated_fraction_interleaved(p_dev, n, v_st, max(m_mb, 2 * p_dev)), 4),
+           "warmup_cooldown_bound_(p-1)/(nvm)": round((p_dev - 1.0) / (n * v_st * m_mb), 5), "bubble_fraction": {}}
     for mode in (None, "pairwise", "balanced", "ideal"):
-        r = simulate(p_dev, n, m_mb, t["F"], t["B"], exchange=mode)
+        r = simulate_interleaved(p_dev, n, m_mb, v_st, t["F"], t["B"], exchange=mode)
         res["bubble_fraction"][mode or "no_exchange"] = round(r["bubble_fraction"], 5)
-    # the same with aligned columns of passes (each as long as its slowest pass): bubble of the last device
-    res["lockstep_last_device_bubble_fraction"] = {
-        (mode or "no_exchange"): round(simulate_lockstep(p_dev, n, m_mb, t["F"], t["B"], exchange=mode)["bubble_fraction"][-1], 5)
-        for mode in (None, "pairwise", "balanced", "ideal")}
-    res["long_context_figure_(p-1)p/((n+1)nm)"] = round((p_dev - 1.0) * p_dev / ((n + 1.0) * n * m_mb), 5)
+    # the same with aligned columns of passes (each as long as its slowest pass): bubble of the last device, and the
+    # part of it that the paper's closed forms count (the columns the device has no pass in)
+    lock = {mode: simulate_lockstep(p_dev, n, m_mb, t["F"], t["B"], exchange=mode, v=v_st) for mode in (None, "pairwise", "balanced", "ideal")}
+    res["lockstep_last_device_bubble_fraction"] = {(mode or "no_exchange"): round(r["bubble_fraction"][-1], 5) for mode, r in lock.items()}
+    res["lockstep_last_device_absent_columns_fraction"] = round(lock["ideal"]["absent_fraction"][-1], 5)
+    res["long_context_figure_(p-1)p/((n+1)nvm)"] = round((p_dev - 1.0) * p_dev / ((n + 1.0) * n * v_st * m_mb), 5)
     return res
 
 

@@ -144,6 +144,8 @@ def test_lockstep_model_and_the_long_context_figure():
         everywhere = simulate_lockstep(p, n, m, tf, tb, exchange="ideal", partial_columns=True)
         lo, hi = everywhere["bubble_fraction"][-1], full_only["bubble_fraction"][-1]
         assert lo <= paper + 1e-12 and paper <= hi + 1e-12, (p, n, m, lo, paper, hi)
+        # the figure itself: the columns the last device has no pass in (slices 1..p-1 only), nothing else
+        assert abs(full_only["absent_fraction"][-1] - paper) < 1e-12
         # the two ends in closed form: columns without the last device at their mean / heaviest pass, and the
         # waits of the last device in the incomplete columns it shares
         assert abs(lo - (p - 1.0) * (p + 2) / (2.0 * m * n * (n + 1))) < 1e-12
@@ -155,3 +157,115 @@ def test_lockstep_model_and_the_long_context_figure():
         assert plain["makespan"] > full_only["makespan"] or p == 1
         if n >= 2 * p:
             assert plain["bubble_fraction"][-1] > 3 * hi
+
+
+# ---- the interleaving form: Fig. interleaved_slim_schedule and the SlimPipe row of Table sched-comparison ----
+with open(os.path.join(os.path.dirname(__file__), "golden", "interleaved_slim_schedule.json")) as f:
+    IFIG = json.load(f)
+
+
+def drawn_passes(dev):
+    """[(kind, microbatch, slice, stage, drawn start)] of a device, 0-based, from the figure's boxes (forward boxes are
+    one unit wide, backward boxes two; the microbatch is the occurrence count of the box's label)."""
+    x, seen, out = 0, {}, []
+    for kind, stage, num in IFIG["drawn"][str(dev)]:
+        if kind == "-":
+            x += num
+            continue
+        k = seen.get((kind, stage, num), 0)
+        seen[(kind, stage, num)] = k + 1
+        out.append((kind, k, num - 1, stage - 1, x))
+        x += 1 if kind == "F" else 2
+    return out, x
+
+
+def test_interleaved_pass_order_of_the_figure():
+    from paper_2504_14519_amd.schedule_sim import device_order_interleaved, simulate_interleaved
+    p, n, m, v = IFIG["p"], IFIG["n"], IFIG["m"], IFIG["v"]
+    widths = []
+    for dev in range(1, p + 1):
+        drawn, width = drawn_passes(dev)
+        widths.append(width)
+        assert len(drawn) == 2 * n * m * v
+        assert [d[:4] for d in drawn] == device_order_interleaved(p, n, m, v, dev - 1)      # every pass of the figure
+    # the timeline under the figure's box widths (a forward pass of one stage 1 unit, a backward pass 2)
+    r = simulate_interleaved(p, n, m, v, [1.0 * v] * n, [2.0 * v] * n)
+    assert r["makespan"] == max(widths) == 105
+    assert abs(r["bubble_fraction"] - 9.0 / 96.0) < 1e-12 and 9.0 / 96.0 == (p - 1.0) / (n * v * m)
+    for dev in range(1, p + 1):
+        drawn, _ = drawn_passes(dev)
+        starts = [t[4] for t in r["timeline"][dev - 1]]
+        # the last device is drawn exactly as simulated; the others never start a pass later than drawn (the figure
+        # shifts some warm-up forward passes to the right to line them up with the other devices' passes)
+        if dev == p:
+            assert starts == [float(d[4]) for d in drawn]
+        assert all(s <= d[4] for s, d in zip(starts, drawn))
+        assert r["timeline"][dev - 1][-1][5] <= widths[dev - 1]
+
+
+def test_interleaved_table_closed_forms():
+    from paper_2504_14519_amd.schedule_sim import (device_order_interleaved, accumulated_units_interleaved,
+                                                   accumulated_fraction_interleaved, simulate_interleaved, simulate_lockstep)
+    for p, n, m, v in [(4, 8, 2, 2), (4, 8, 4, 2), (8, 16, 4, 3), (4, 12, 3, 1), (8, 8, 2, 5), (2, 4, 3, 4), (16, 32, 2, 2)]:
+        # activation memory: 1/p + 2(p-1)/(nvp) of M_a on the first device, less on the later ones
+        if m * n * v >= n * v + 2 * (p - 1):
+            assert accumulated_units_interleaved(p, n, m, v, 0) == n * v + 2 * (p - 1)
+            assert abs(accumulated_fraction_interleaved(p, n, v, m) - (1.0 / p + 2.0 * (p - 1) / (n * v * p))) < 1e-12
+            assert [accumulated_units_interleaved(p, n, m, v, r) for r in range(p)] == [n * v + 2 * (p - 1 - r) for r in range(p)]
+        # bubble fraction (p-1)/(nvm) for slice-independent pass times: event simulation and lockstep columns
+        for tf, tb in ((1.0, 2.0), (0.7, 1.9)):
+            r = simulate_interleaved(p, n, m, v, [tf] * n, [tb] * n)
+            assert abs(r["bubble_fraction"] - (p - 1.0) / (n * v * m)) < 1e-9
+            assert abs(r["makespan"] - (m * n * v + p - 1) * (tf + tb) / v) < 1e-9
+            u = simulate_lockstep(p, n, m, [tf] * n, [tb] * n, v=v)
+            assert all(abs(f - (p - 1.0) / (n * v * m)) < 1e-12 for f in u["bubble_fraction"])
+            assert abs(u["absent_fraction"][-1] - (p - 1.0) / (n * v * m)) < 1e-12
+        # "extremely long context": pass time proportional to the attended key-value length.  The columns the last
+        # device is absent from hold slices 1..p-1 only: (p-1)p/((n+1)nvm), the table's footnote, exactly
+        tf = [float(L) for L in range(1, n + 1)]
+        tb = [2.0 * L for L in range(1, n + 1)]
+        u = simulate_lockstep(p, n, m, tf, tb, exchange="ideal", v=v)
+        assert abs(u["absent_fraction"][-1] - (p - 1.0) * p / ((n + 1.0) * n * v * m)) < 1e-12
+        assert u["absent_fraction"][-1] < (p - 1.0) / (n * v * m) or n == p == 1
+        # every pass once, backward after forward, and v = 1 is the plain schedule
+        for rank in (0, p - 1):
+            order = device_order_interleaved(p, n, m, v, rank)
+            assert sorted(order) == sorted((kd, k, i, c) for kd in "FB" for k in range(m) for i in range(n) for c in range(v))
+            at = {o: j for j, o in enumerate(order)}
+            assert all(at[("F", k, i, c)] < at[("B", k, i, c)] for k in range(m) for i in range(n) for c in range(v))
+            if v == 1:
+                assert [o[:3] for o in order] == device_order(p, n, m, rank)
+    # v = 1: same timeline as the plain simulator, with the context exchange
+    p, n, m = 4, 8, 3
+    tf, tb = [1.0 + 0.3 * L for L in range(n)], [2.0 + 0.8 * L for L in range(n)]
+    for mode in (None, "pairwise", "balanced", "ideal"):
+        a = simulate(p, n, m, tf, tb, exchange=mode, t_other_fwd=0.5, t_other_bwd=1.0, t_send=0.1)
+        b = simulate_interleaved(p, n, m, 1, tf, tb, exchange=mode, t_other_fwd=0.5, t_other_bwd=1.0, t_send=0.1)
+        assert abs(a["makespan"] - b["makespan"]) < 1e-9 and abs(a["bubble_fraction"] - b["bubble_fraction"]) < 1e-12
+
+
+def test_interleaved_dependencies_and_exchange():
+    from paper_2504_14519_amd.schedule_sim import simulate_interleaved
+    p, n, m, v = 4, 8, 2, 2
+    tf = [float(L) for L in range(1, n + 1)]
+    tb = [2.0 * L for L in range(1, n + 1)]
+    plain = simulate_interleaved(p, n, m, v, tf, tb)
+    for mode in ("pairwise", "balanced", "ideal"):
+        r = simulate_interleaved(p, n, m, v, tf, tb, exchange=mode, t_send=0.05)
+        assert abs(sum(r["busy"]) - sum(plain["busy"])) < 1e-6          # the exchange moves work, it creates none
+        assert r["bubble_fraction"] < plain["bubble_fraction"]
+        end = {(kd, d, k, i, c): e for d in range(p) for kd, k, i, c, s, e in r["timeline"][d]}
+        for d in range(p):
+            t = 0.0
+            for kd, k, i, c, s, e in r["timeline"][d]:
+                assert s >= t - 1e-12 and e > s
+                t = e
+                stage = c * p + d
+                if kd == "F" and stage > 0:
+                    prev = (stage - 1) % p, (stage - 1) // p
+                    assert s >= end[("F", prev[0], k, i, prev[1])] + (0.05 if prev[0] != d else 0.0) - 1e-12
+                if kd == "B":
+                    assert s >= end[("F", d, k, i, c)]
+                    if stage < p * v - 1:
+                        nxt = (stage + 1) % p, (stage + 1) // p
+                        assert s >= end[("B", nxt[0], k, i, nxt[1])] + (0.05 if nxt[0] != d else 0.0) - 1e-12
