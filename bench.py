@@ -235,6 +235,13 @@ def main():
     # random operands the chip is power limited, which is the regime the attention kernels run in
     roofline["mfma_stream_tflops"] = {"constant_operands": round(sp.slimpipe_attn_mfma_rate(False), 1),
                                       "random_operands": round(sp.slimpipe_attn_mfma_rate(True), 1)}
+    # the same matrix work on every compute unit, timed per XCD: workgroups are handed to the XCDs round-robin, so the
+    # slowest XCD sets the time of a launch of equal workgroups (what the other XCDs idle at its end is lost)
+    xr = sp.slimpipe_attn_xcd_rate()
+    ends = [e for _, _, e in xr.values()]
+    roofline["xcd_spread"] = {"mean_workgroup_ms_by_xcd": {str(x): round(m_, 3) for x, (_, m_, _) in xr.items()},
+                              "last_end_ms_by_xcd": {str(x): round(e, 3) for x, (_, _, e) in xr.items()},
+                              "slowest_over_mean": round(max(ends) / (sum(ends) / len(ends)), 4)}
     roofline["issued_frac_of_mfma_stream_random"] = round(roofline["achieved_issued"] / max(roofline["mfma_stream_tflops"]["random_operands"], 1e-9), 4)
 
     out = {

@@ -31,6 +31,13 @@ int slimpipe_attn_profile_read(double total_ms[SLIMPIPE_KERNEL_KINDS], int64_t l
  * sink: device pointer to at least one float (never written in practice). */
 int slimpipe_attn_mfma_rate(int random_operands, float* sink, double* tflops, void* hip_stream);
 
+/* How evenly the XCDs of the GPU run the same work.  Launches `workgroups` workgroups of 8 waves that each issue 4 * iters
+ * bf16 matrix instructions on random operands and writes, per workgroup, its start and end time (ticks of the constant
+ * 100 MHz wall clock) and the XCD it ran on into the three DEVICE arrays (workgroups entries each).  Waits for the kernel.
+ * The hardware hands workgroups to the XCDs round-robin whatever their speed, so a launch of equal workgroups ends when
+ * the slowest XCD ends; bench.py reports the per-XCD times as `xcd_spread`. */
+int slimpipe_attn_xcd_rate(int32_t iters, int32_t workgroups, int64_t* t_start, int64_t* t_end, uint32_t* xcc, void* hip_stream);
+
 /* What float32 atomic adds into dq would cost a backward kernel that computes the scores once (key-stationary, dK/dV
  * in registers, dQ added into memory).  Launches key_tiles * heads workgroups of 8 waves; each walks the s_q /
  * rows_per_step query tiles of one head and per tile adds 1.0f to a rows_per_step x 128 block of dq

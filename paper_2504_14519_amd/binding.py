@@ -81,6 +81,8 @@ def _load():
     L.slimpipe_attn_mfma_rate.restype = ctypes.c_int
     L.slimpipe_attn_dq_atomic_probe.argtypes = [vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
     L.slimpipe_attn_dq_atomic_probe.restype = ctypes.c_int
+    L.slimpipe_attn_xcd_rate.argtypes = [i32, i32, vp, vp, vp, vp]
+    L.slimpipe_attn_xcd_rate.restype = ctypes.c_int
     L.slimpipe_attn_profile_enable.argtypes = [ctypes.c_int]
     L.slimpipe_attn_profile_enable.restype = ctypes.c_int
     L.slimpipe_attn_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
@@ -348,6 +350,24 @@ def slimpipe_attn_dq_atomic_probe(s_q, heads, key_tiles, rows_per_step, placemen
     want = float(key_tiles * (64 // rows_per_step)) if with_atomics else 0.0
     ok = bool((dq == want).all())
     return ms.value, ok, int(mism.item())
+
+
+def slimpipe_attn_xcd_rate(iters=20000, rounds=4):
+    """-> {xcd: (workgroups, mean workgroup ms, last end ms)} for `rounds` workgroups of equal matrix work per compute unit."""
+    import torch
+    n = rounds * torch.cuda.get_device_properties(0).multi_processor_count
+    t0 = torch.zeros(n, device="cuda", dtype=torch.int64)
+    t1 = torch.zeros(n, device="cuda", dtype=torch.int64)
+    xcc = torch.zeros(n, device="cuda", dtype=torch.int32)
+    for _ in range(2):          # the second launch is the one reported (clocks settled)
+        _check(lib.slimpipe_attn_xcd_rate(iters, n, t0.data_ptr(), t1.data_ptr(), xcc.data_ptr(), _stream()), "xcd_rate")
+    t0, t1, xcc = t0.cpu(), t1.cpu(), xcc.cpu()
+    base = int(t0.min())
+    out = {}
+    for x in sorted(set(xcc.tolist())):
+        sel = xcc == x
+        out[int(x)] = (int(sel.sum()), float((t1[sel] - t0[sel]).double().mean()) / 1e5, float(int(t1[sel].max()) - base) / 1e5)
+    return out
 
 
 def slimpipe_attn_profile_enable(enable):

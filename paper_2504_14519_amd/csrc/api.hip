@@ -582,6 +582,15 @@ int slimpipe_attn_mfma_rate(int random_operands, float* sink, double* tflops, vo
   return rc;
 }
 
+int slimpipe_attn_xcd_rate(int32_t iters, int32_t workgroups, int64_t* t_start, int64_t* t_end, uint32_t* xcc, void* hip_stream) {
+  if (!t_start || !t_end || !xcc) return SLIMPIPE_EINVAL_NULL;
+  if (iters < 1 || workgroups < 1 || workgroups > 1 << 16) return SLIMPIPE_EINVAL_SHAPE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (launch_xcd_rate(iters, workgroups, reinterpret_cast<long long*>(t_start), reinterpret_cast<long long*>(t_end), xcc, st) != hipSuccess)
+    return SLIMPIPE_ELAUNCH;
+  return hipStreamSynchronize(st) == hipSuccess ? SLIMPIPE_OK : SLIMPIPE_ELAUNCH;
+}
+
 int slimpipe_attn_dq_atomic_probe(float* dq, int32_t s_q, int32_t heads, int32_t key_tiles, int32_t rows_per_step,
                                   int32_t placement, int32_t rotate, int32_t filler_mfma, int32_t with_atomics,
                                   uint32_t* xcc_mismatch, double* ms, void* hip_stream) {

@@ -134,6 +134,45 @@ hipError_t launch_mfma_rate(int random, int iters, int workgroups, float* sink, 
   return hipGetLastError();
 }
 
+// ---- measurement aid: how evenly the eight XCDs of the chip run the same work ----
+// Every workgroup issues the same number of matrix instructions (random operands) and records when it started and
+// ended (constant-rate wall clock) and the XCD it ran on.  Workgroups are handed to the XCDs round-robin whatever
+// their speed, so a launch of equal workgroups ends when the slowest XCD ends.
+__global__ __launch_bounds__(512) void xcd_rate_kernel(int iters, long long* t_start, long long* t_end, unsigned* xcc) {
+  const long long t0 = wall_clock64();
+  const unsigned tid = threadIdx.x + 512u * blockIdx.x;
+  bf16x8 a[2], b[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      unsigned ha = (tid * 64u + i * 16u + j) * 2654435761u, hb = (tid * 64u + i * 16u + 8u + j) * 2246822519u;
+      ha ^= ha >> 15; hb ^= hb >> 13;
+      a[i][j] = __builtin_bit_cast(bf16_t, (unsigned short)(((0x77u + (ha & 7u)) << 7) | ((ha >> 8) & 0x7fu) | ((ha >> 16) & 0x8000u)));
+      b[i][j] = __builtin_bit_cast(bf16_t, (unsigned short)(((0x77u + (hb & 7u)) << 7) | ((hb >> 8) & 0x7fu) | ((hb >> 16) & 0x8000u)));
+    }
+  f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+  for (int it = 0; it < iters; ++it) {
+    c0 = mfma32(a[0], b[0], c0);
+    c1 = mfma32(a[1], b[1], c1);
+    c2 = mfma32(a[0], b[1], c2);
+    c3 = mfma32(a[1], b[0], c3);
+  }
+  float t = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) t += c0[i] + c1[i] + c2[i] + c3[i];
+  if (threadIdx.x == 0) {
+    t_start[blockIdx.x] = t0;
+    t_end[blockIdx.x] = wall_clock64() + (t == 12345.678f ? 1 : 0);      // (keeps the loop alive)
+    xcc[blockIdx.x] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));   // XCC_ID, bits 3:0
+  }
+}
+
+hipError_t launch_xcd_rate(int iters, int workgroups, long long* t_start, long long* t_end, unsigned* xcc, hipStream_t st) {
+  hipLaunchKernelGGL(xcd_rate_kernel, dim3((unsigned)workgroups), dim3(512), 0, st, iters, t_start, t_end, xcc);
+  return hipGetLastError();
+}
+
 // ---- measurement aid: what float32 atomic adds cost in the access pattern of a fused backward ----
 // A backward kernel that computes S and dP once would be key-stationary (dK/dV stay in registers, summed in a
 // fixed order) and would have to ADD its dQ contributions into memory: per step a workgroup of 8 waves owning

@@ -821,20 +821,26 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
       vdst = a.dv_acc[kchunk] + base;
       accumulate = a.dkv_accumulate != 0;
     }
+    // One gradient at a time.  When the call adds to the accumulators, all 16 loads of the old values are issued
+    // before the first of them is needed: a load, add, store chain per 16 bytes pays the memory latency 16 times over
+    // (a store may alias a later load for all the compiler knows, so it does not batch them by itself), and with few
+    // query tiles per key tile (many KV heads, short slices) that was a sixth of the kernel's time.
+    auto flush = [&](const f32x16 (&acc)[DB], float* dst, float factor) {
+      f32x4 old[DB * 4];
+      if (accumulate) {
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int i4 = 0; i4 < 4; ++i4) {
-        const int d = 32 * db + 8 * i4 + 4 * g_out;
-        f32x4 k4 = {st.dk[db][4 * i4] * a.scale, st.dk[db][4 * i4 + 1] * a.scale, st.dk[db][4 * i4 + 2] * a.scale,
-                    st.dk[db][4 * i4 + 3] * a.scale};
-        f32x4 v4 = {st.dv[db][4 * i4], st.dv[db][4 * i4 + 1], st.dv[db][4 * i4 + 2], st.dv[db][4 * i4 + 3]};
-        f32x4* kd = reinterpret_cast<f32x4*>(kdst + d);
-        f32x4* vd = reinterpret_cast<f32x4*>(vdst + d);
-        if (accumulate) { k4 += *kd; v4 += *vd; }
-        *kd = k4;
-        *vd = v4;
+        for (int j = 0; j < DB * 4; ++j) old[j] = *reinterpret_cast<const f32x4*>(dst + 32 * (j >> 2) + 8 * (j & 3) + 4 * g_out);
       }
+#pragma unroll
+      for (int j = 0; j < DB * 4; ++j) {
+        const int db = j >> 2, i4 = j & 3;
+        f32x4 x4 = {acc[db][4 * i4] * factor, acc[db][4 * i4 + 1] * factor, acc[db][4 * i4 + 2] * factor, acc[db][4 * i4 + 3] * factor};
+        if (accumulate) x4 += old[j];
+        *reinterpret_cast<f32x4*>(dst + 32 * db + 8 * i4 + 4 * g_out) = x4;
+      }
+    };
+    flush(st.dk, kdst, a.scale);
+    flush(st.dv, vdst, 1.0f);
   }
 }
 

@@ -103,6 +103,7 @@ hipError_t launch_merge(const MergeArgs& a, hipStream_t st);
 hipError_t launch_finalize(const float* acc, __bf16* dst, int64_t n, hipStream_t st);
 hipError_t launch_dq_atomic_probe(float* dq, int s_q, int heads, int key_tiles, int rows_per_step, int placement, int rotate,
                                   int filler_mfma, int with_atomics, unsigned* xcc_mismatch, hipStream_t st);
+hipError_t launch_xcd_rate(int iters, int workgroups, long long* t_start, long long* t_end, unsigned* xcc, hipStream_t st);
 hipError_t launch_mfma_rate(int random, int iters, int workgroups, float* sink, hipStream_t st);
 
 }  // namespace slimpipe
