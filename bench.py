@@ -221,7 +221,7 @@ def main():
         "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": stored_traffic(c["name"], dom),
         "flop_accounting": "credited: %g*D per visible pair and q head for %s (S and dP, which both backward kernels "
                            "compute, counted once and split between them); the kernel issues %g*D" % (credited[dom], dom, issued[dom]),
-        "achieved_issued": round(rate(issued[dom], dom_ms), 1),
+        "achieved_issued": round(rate(issued[dom], dom_ms), 1), "frac_issued": round(rate(issued[dom], dom_ms) / PEAK_BF16_TFLOPS, 4),
         "launches": int(dom_n), "avg_launch_ms": round(dom_ms / max(1, dom_n), 4),
         "flops_per_launch_avg_credited": credited[dom] * per_d / max(1, dom_n),
         "kernel_ms_per_step": {kk: round(prof[kk][0] / args.steps, 3) for kk in prof},
