@@ -89,13 +89,17 @@ int slimpipe_attn_init(void);
  * backward needs).  No device access. */
 int slimpipe_attn_validate(const slimpipe_attn_params* p, int is_bwd);
 
-/* Bytes of device workspace the call would like.  Forward: 0 unless the call is a short slice over a long
- * cache whose query blocks leave compute units idle; then room for the float32 partial (out, lse) of the 2 to 16
+/* Bytes of device workspace the call would like.  Forward: 256 bytes for a counter through which the workgroups take
+ * their work items (see the backward below), plus, when the call is a short slice over a long cache whose query
+ * blocks leave compute units idle, room for the float32 partial (out, lse) of the 2 to 16
  * key ranges of equal work the call is cut into (see slimpipe_attn_fwd).  Backward needs two floats per
  * (batch, q head, row): delta = rowsum(d_out * out) (kept negated) and lse in log2 units, each array rounded up to
- * 256 bytes; slimpipe_attn_bwd refuses less.  On top of that it can use room for partial dk/dv sums:
- * when the key tiles of a call do not fill the GPU's compute units evenly, the query rows of each
- * key tile are cut into 2, 4 or 8 chunks that run as workgroups of their own, each writing float32
+ * 256 bytes; slimpipe_attn_bwd refuses less.  On top of that it can use, in this order: 256 bytes for a counter
+ * through which the workgroups of the dk/dv kernel take their work items (the hardware hands workgroups to the
+ * chip's eight XCDs in turn whatever their speed; with the counter a faster XCD takes more items; the results do
+ * not depend on who computes what), and room for partial dk/dv sums: when the key tiles of a call do not fill the
+ * GPU's compute units evenly, or when the counter is there and more items make for a more even finish, the query
+ * rows of each key tile are cut into 2, 4 or 8 chunks that run as workgroups of their own, each writing float32
  * partial sums [chunk][dk, dv][batch][kv head][keys rounded up to 256][head_dim] that a second kernel adds up
  * in chunk order.  The figure returned here includes that room for the split this call would pick;
  * given less, slimpipe_attn_bwd uses the largest split that fits (down to none).  In the same way the dq
@@ -107,11 +111,14 @@ int slimpipe_attn_workspace_bytes(const slimpipe_attn_params* p, int is_bwd, siz
 /* Forward of one query slice against keys [kv_begin, kv_end) of the cached prefix
  * (Sec. 4.1.2; partial ranges: Sec. 4.2.2).  Writes out (dtype p->out_dtype, strides o_*) and
  * lse [batch, n_q_heads, s_q].  Scores are never stored.
- *   workspace : may be NULL.  Given slimpipe_attn_workspace_bytes(p, 0) > 0 bytes, a call whose query blocks
- *               would not fill the GPU cuts [kv_begin, kv_end) into ranges of equal work (cut points on
- *               multiples of 256 keys), computes them in one launch into float32 partials in the workspace and
- *               merges them (the rule of slimpipe_attn_merge) into (out, lse) in the same call; given less
- *               room it uses as many ranges as fit, down to the undivided computation. */
+ *   workspace : may be NULL (16-byte aligned otherwise).  Its first 256 bytes, when it has them, hold the counter
+ *               through which the workgroups take their work items (set to zero by a one-thread kernel ahead of
+ *               the forward kernel; the results do not depend on it).  Given slimpipe_attn_workspace_bytes(p, 0)
+ *               bytes, a call whose query blocks would not fill the GPU cuts [kv_begin, kv_end) into ranges of
+ *               equal work (cut points on multiples of 256 keys), computes them in one launch into float32
+ *               partials behind the counter and merges them (the rule of slimpipe_attn_merge) into (out, lse)
+ *               in the same call; given less room it uses as many ranges as fit, down to the undivided
+ *               computation. */
 int slimpipe_attn_fwd(const slimpipe_attn_params* p,
                       const void* q_slice, const void* k_prefix, const void* v_prefix,
                       void* out, float* lse,

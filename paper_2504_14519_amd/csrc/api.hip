@@ -79,7 +79,7 @@ int64_t dkdv_key_tiles(const slimpipe_attn_params* p, int n_chunks) {
   const int64_t per = dkdv_keys_per_workgroup();
   return (p->kv_end - kv_grid_origin(p->kv_begin, n_chunks, (int)per) + per - 1) / per;
 }
-int preferred_split(const slimpipe_attn_params* p, int n_chunks) {
+int preferred_split(const slimpipe_attn_params* p, int n_chunks, bool ticket) {
   const int64_t tiles = dkdv_key_tiles(p, n_chunks);
   const int64_t w = tiles * p->n_kv_heads * p->batch;
   if (w <= 0) return 1;
@@ -92,10 +92,18 @@ int preferred_split(const slimpipe_attn_params* p, int n_chunks) {
     cost[i] = (s > 1 && stream / s < 64) ? 1e30 : (double)((w * s + cus - 1) / cus) / s;
     if (cost[i] < best) best = cost[i];
   }
-  for (int i = 0; i < 4; ++i)
-    if (cost[i] <= best * 1.03) return 1 << i;
-  return 1;
+  int split = 1;
+  for (int i = 3; i >= 0; --i)
+    if (cost[i] <= best * 1.03) split = 1 << i;
+  // Items handed out through a counter: a compute unit that finishes early takes another one, so more items even out
+  // compute units (and XCDs) of unequal speed and key tiles of unequal streams (the causal diagonal).  Up to about 16
+  // items per compute unit, as long as a chunk keeps at least 128 query tiles.
+  if (ticket)
+    while (split < 8 && w * split < 16 * (int64_t)cus && stream / (2 * split) >= 128) split *= 2;
+  return split;
 }
+// room for the ticket counter of the dk/dv kernel behind the two statistics arrays
+constexpr size_t kTicketBytes = 256;
 size_t split_bytes(const slimpipe_attn_params* p, int n_chunks, int split) {
   if (split <= 1) return 0;
   return (size_t)split * 2 * (size_t)p->batch * (size_t)p->n_kv_heads *
@@ -272,11 +280,11 @@ int slimpipe_attn_workspace_bytes(const slimpipe_attn_params* p, int is_bwd, siz
   if (!bytes) return SLIMPIPE_EINVAL_NULL;
   int rc = slimpipe_attn_validate(p, is_bwd);
   if (rc != SLIMPIPE_OK) return rc;
-  if (!is_bwd) { *bytes = fwd_parts_bytes(p, fwd_preferred_ranges(p)); return SLIMPIPE_OK; }
+  if (!is_bwd) { *bytes = kTicketBytes + fwd_parts_bytes(p, fwd_preferred_ranges(p)); return SLIMPIPE_OK; }
   // the tile grid of a chunked call can start up to 255 keys before kv_begin: room for whichever of the
   // two variants asks for more
-  const size_t one = split_bytes(p, 1, preferred_split(p, 1)), many = split_bytes(p, 2, preferred_split(p, 2));
-  *bytes = delta_bytes(p) + (one > many ? one : many) + dq_parts_bytes(p, fwd_preferred_ranges(p));
+  const size_t one = split_bytes(p, 1, preferred_split(p, 1, true)), many = split_bytes(p, 2, preferred_split(p, 2, true));
+  *bytes = delta_bytes(p) + kTicketBytes + (one > many ? one : many) + dq_parts_bytes(p, fwd_preferred_ranges(p));
   return SLIMPIPE_OK;
 }
 
@@ -287,7 +295,7 @@ int slimpipe_attn_workspace_bytes(const slimpipe_attn_params* p, int is_bwd, siz
 static int fwd_impl(const slimpipe_attn_params* p, const void* q_slice, const void* const* k_chunks,
                     const void* const* v_chunks, int32_t n_chunks, int64_t chunk_len, int32_t n_ranges,
                     const int64_t* range_begin, const int64_t* range_end, float* part_out, int64_t part_out_elems,
-                    float* part_lse, int64_t part_lse_elems, void* out, float* lse, void* hip_stream) {
+                    float* part_lse, int64_t part_lse_elems, void* out, float* lse, void* hip_stream, unsigned* ticket = nullptr) {
   int rc = slimpipe_attn_validate(p, 0);
   if (rc != SLIMPIPE_OK) return rc;
   const bool parts = part_out != nullptr;
@@ -335,8 +343,14 @@ static int fwd_impl(const slimpipe_attn_params* p, const void* q_slice, const vo
     a.out_range_stride = 0; a.lse_range_stride = 0;
     a.o_stride_b = p->o_stride_b; a.o_stride_s = p->o_stride_s; a.o_stride_h = p->o_stride_h;
   }
+  a.ticket = ticket;
+  a.items[0] = (p->s_q + 255) / 256;
+  a.items[1] = p->n_q_heads;
+  a.items[2] = p->batch * n_ranges;
+  if ((int64_t)a.items[0] * a.items[1] * a.items[2] > (int64_t)1 << 30) return SLIMPIPE_EINVAL_SHAPE;
   if (ensure_device_ready() != SLIMPIPE_OK) return SLIMPIPE_ELAUNCH;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (ticket && launch_zero_counter(ticket, st) != hipSuccess) return SLIMPIPE_ELAUNCH;
   hipError_t e = timed(SLIMPIPE_KERNEL_FWD, st, [&] { return launch_fwd(a, p->batch, p->head_dim, st); });
   if (e != hipSuccess) return SLIMPIPE_ELAUNCH;
   if (parts && out) {
@@ -363,19 +377,23 @@ static int fwd_auto(const slimpipe_attn_params* p, const void* q_slice, const vo
                     void* workspace, size_t workspace_bytes, void* hip_stream) {
   int rc = slimpipe_attn_validate(p, 0);
   if (rc != SLIMPIPE_OK) return rc;
+  // workspace: [ticket counter, 256 bytes][partial out of the ranges][partial lse of the ranges]
+  if (workspace && !aligned16(workspace)) return SLIMPIPE_EINVAL_ALIGN;
+  unsigned* ticket = (workspace && workspace_bytes >= kTicketBytes) ? static_cast<unsigned*>(workspace) : nullptr;
+  char* parts_base = ticket ? static_cast<char*>(workspace) + kTicketBytes : static_cast<char*>(workspace);
+  const size_t parts_room = ticket ? workspace_bytes - kTicketBytes : workspace_bytes;
   int ranges = workspace ? fwd_preferred_ranges(p) : 1;
-  while (ranges > 1 && (fwd_parts_bytes(p, ranges) > workspace_bytes || (int64_t)p->batch * ranges > 65535)) --ranges;
+  while (ranges > 1 && (fwd_parts_bytes(p, ranges) > parts_room || (int64_t)p->batch * ranges > 65535)) --ranges;
   if (ranges <= 1)
     return fwd_impl(p, q_slice, k_chunks, v_chunks, n_chunks, chunk_len, 1, &p->kv_begin, &p->kv_end, nullptr, 0, nullptr, 0, out,
-                    lse, hip_stream);
-  if (!aligned16(workspace)) return SLIMPIPE_EINVAL_ALIGN;
+                    lse, hip_stream, ticket);
   int64_t begin[kMaxRanges], end[kMaxRanges];
   equal_work_ranges(p, ranges, begin, end);
-  float* part_out = static_cast<float*>(workspace);
-  float* part_lse = reinterpret_cast<float*>(static_cast<char*>(workspace) + (size_t)ranges * fwd_part_out_bytes(p));
+  float* part_out = reinterpret_cast<float*>(parts_base);
+  float* part_lse = reinterpret_cast<float*>(parts_base + (size_t)ranges * fwd_part_out_bytes(p));
   return fwd_impl(p, q_slice, k_chunks, v_chunks, n_chunks, chunk_len, ranges, begin, end, part_out,
                   (int64_t)(fwd_part_out_bytes(p) / sizeof(float)), part_lse, (int64_t)(stat_bytes(p) / sizeof(float)), out, lse,
-                  hip_stream);
+                  hip_stream, ticket);
 }
 
 int slimpipe_attn_fwd(const slimpipe_attn_params* p, const void* q_slice, const void* k_prefix,
@@ -442,12 +460,17 @@ static int bwd_impl(const slimpipe_attn_params* p, const void* q_slice, const vo
   a.lse = lse;
   a.delta = static_cast<float*>(workspace);
   a.lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + stat_bytes(p));
-  int split = preferred_split(p, n_chunks);
-  while (split > 1 && delta_bytes(p) + split_bytes(p, n_chunks, split) > workspace_bytes) split /= 2;
+  // behind the statistics: the ticket counter of the dk/dv kernel (when there is room for it), the partial dk/dv sums
+  // of a split query stream, the partial dq of key ranges
+  const bool ticket = workspace_bytes >= delta_bytes(p) + kTicketBytes;
+  const size_t fixed = delta_bytes(p) + (ticket ? kTicketBytes : 0);
+  a.ticket = ticket ? reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + delta_bytes(p)) : nullptr;
+  int split = preferred_split(p, n_chunks, ticket);
+  while (split > 1 && fixed + split_bytes(p, n_chunks, split) > workspace_bytes) split /= 2;
   a.n_split = split;
-  a.part = reinterpret_cast<float*>(static_cast<char*>(workspace) + delta_bytes(p));
+  a.part = reinterpret_cast<float*>(static_cast<char*>(workspace) + fixed);
   // what is left of the workspace takes the partial dq of as many key ranges as fit
-  const size_t used = delta_bytes(p) + split_bytes(p, n_chunks, split);
+  const size_t used = fixed + split_bytes(p, n_chunks, split);
   int dq_ranges = fwd_preferred_ranges(p);
   while (dq_ranges > 1 && (used + dq_parts_bytes(p, dq_ranges) > workspace_bytes || (int64_t)p->batch * dq_ranges > 65535)) --dq_ranges;
   a.n_dq_ranges = dq_ranges;
@@ -466,6 +489,14 @@ static int bwd_impl(const slimpipe_attn_params* p, const void* q_slice, const vo
   a.dq_final = dq;
   a.dq_final_f32 = (dq_dtype == SLIMPIPE_F32); a.dq_final_accumulate = dq_accumulate ? 1 : 0;
   a.nkeys_pad = dkdv_key_tiles(p, n_chunks) * dkdv_keys_per_workgroup();
+  a.dkdv_items[0] = (int32_t)(dkdv_key_tiles(p, n_chunks) * split);
+  a.dkdv_items[1] = p->n_kv_heads;
+  a.dkdv_items[2] = p->batch;
+  a.dq_items[0] = (p->s_q + 255) / 256;
+  a.dq_items[1] = p->n_q_heads;
+  a.dq_items[2] = p->batch * dq_ranges;
+  if ((int64_t)a.dq_items[0] * a.dq_items[1] * a.dq_items[2] > (int64_t)1 << 30) return SLIMPIPE_EINVAL_SHAPE;
+  if ((int64_t)a.dkdv_items[0] * a.dkdv_items[1] * a.dkdv_items[2] > (int64_t)1 << 30) return SLIMPIPE_EINVAL_SHAPE;
   a.s_q = p->s_q; a.n_q_heads = p->n_q_heads; a.n_kv_heads = p->n_kv_heads;
   a.group = p->n_q_heads / p->n_kv_heads; a.causal = p->causal;
   a.dq_f32 = dq_ranges > 1 ? 1 : a.dq_final_f32; a.dq_accumulate = dq_ranges > 1 ? 0 : a.dq_final_accumulate;

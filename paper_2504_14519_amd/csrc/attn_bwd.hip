@@ -26,6 +26,7 @@ template <int D>
 __global__ __launch_bounds__(256) void attn_delta_kernel(const BwdArgs a, int batch) {
   constexpr int NC = D / 8;
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (gid == 0 && a.ticket) { a.ticket[0] = 0u; a.ticket[1] = 0u; }     // the dk/dv and dq kernels of this call, later on the stream, count from zero
   const int64_t rh = gid / NC;                 // (b, r, h) flattened
   const int c = (int)(gid % NC);
   const int64_t total = (int64_t)batch * a.s_q * a.n_q_heads;
@@ -208,8 +209,23 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);      // known uniform to the compiler
   const bool group_b = wave_u >= NW / 2;
   const int gtid = tid & (GT - 1);
-  const int qblk = (int)gridDim.x - 1 - (int)blockIdx.x;
-  const int h = blockIdx.y, b = (int)blockIdx.z / a.n_dq_ranges, r = (int)blockIdx.z - b * a.n_dq_ranges, hk = h / a.group;
+  // Work item: index -> (query block, q head, batch index x key range), the first fastest: the workgroup's own
+  // index, or the next value of the ticket counter (surplus workgroups leave at once).
+  int item = blockIdx.x;
+  if (a.ticket) {
+    unsigned* slot = reinterpret_cast<unsigned*>(smem);      // (the tile rings are not in use yet)
+    if (threadIdx.x == 0) *slot = atomicAdd(a.ticket + 1, 1u);
+    __syncthreads();
+    item = (int)*slot;
+    __syncthreads();
+    if (item >= a.dq_items[0] * a.dq_items[1] * a.dq_items[2]) return;
+  }
+  item = __builtin_amdgcn_readfirstlane(item);
+  const int per_z = a.dq_items[0] * a.dq_items[1];
+  const int bz = __builtin_amdgcn_readfirstlane(item / per_z), item_xy = item - bz * per_z;
+  const int h = __builtin_amdgcn_readfirstlane(item_xy / a.dq_items[0]), bx = item_xy - h * a.dq_items[0];
+  const int qblk = a.dq_items[0] - 1 - bx;
+  const int b = bz / a.n_dq_ranges, r = bz - b * a.n_dq_ranges, hk = h / a.group;
   const int64_t kv_begin = a.dq_range_begin[r], kv_end = a.dq_range_end[r];      // this workgroup's key range
   const int m0 = qblk * BM, wrow0 = m0 + wave_u * 32;
   const int myrow = wrow0 + ql;
@@ -375,7 +391,9 @@ template <int D, int NW, int BN>
 static hipError_t launch_dq_t(const BwdArgs& a, int batch, hipStream_t st) {
   constexpr int BM = NW * 32;
   static_assert(BM == 256 && BN == kDqKeysPerTile, "dq_lds_bytes assumes this shape");
-  dim3 grid((a.s_q + BM - 1) / BM, a.n_q_heads, batch * a.n_dq_ranges), block(NW * 64);
+  const int64_t items = (int64_t)a.dq_items[0] * a.dq_items[1] * a.dq_items[2];
+  const int64_t wgs = a.ticket ? items + items / 4 + 64 : items;      // (see launch_dkdv_t)
+  dim3 grid((unsigned)wgs), block(NW * 64);
   hipLaunchKernelGGL((attn_bwd_dq_kernel<D, NW, BN>), grid, block, dq_lds_bytes<D>(), st, a);
   return hipGetLastError();
 }
@@ -557,11 +575,25 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);      // known uniform to the compiler
   const bool group_b = wave_u >= NW / 2;
   const int gtid = tid & (GT - 1);
-  const int hk = blockIdx.y, b = blockIdx.z;
-  // blockIdx.x = key tile * n_split + chunk of that tile's query stream
+  // Work item: index -> (key tile * n_split + chunk of that tile's query stream, kv head, batch index), the first
+  // fastest.  Either the workgroup's own index, or the next value of the ticket counter (then the grid holds more
+  // workgroups than items and the surplus ones leave at once).
+  int item = blockIdx.x;
+  if (a.ticket) {
+    unsigned* slot = reinterpret_cast<unsigned*>(smem);      // (the tile rings are not in use yet)
+    if (threadIdx.x == 0) *slot = atomicAdd(a.ticket, 1u);
+    __syncthreads();
+    item = (int)*slot;
+    __syncthreads();
+    if (item >= a.dkdv_items[0] * a.dkdv_items[1] * a.dkdv_items[2]) return;
+  }
   // (the quotients come out of vector instructions: read them back so that the compiler knows they are uniform)
-  const int ktile = __builtin_amdgcn_readfirstlane((int)(blockIdx.x / (unsigned)a.n_split));
-  const int split = (int)blockIdx.x - ktile * a.n_split;
+  item = __builtin_amdgcn_readfirstlane(item);
+  const int per_b = a.dkdv_items[0] * a.dkdv_items[1];
+  const int b = __builtin_amdgcn_readfirstlane(item / per_b), item_hb = item - b * per_b;
+  const int hk = __builtin_amdgcn_readfirstlane(item_hb / a.dkdv_items[0]), item_x = item_hb - hk * a.dkdv_items[0];
+  const int ktile = __builtin_amdgcn_readfirstlane((int)((unsigned)item_x / (unsigned)a.n_split));
+  const int split = item_x - ktile * a.n_split;
   // key tiles sit on the grid of kv_grid_origin (absolute multiples of 256 when K/V are chunked): a tile
   // lies inside one chunk; keys of the first tile before kv_begin are computed and not stored
   const int64_t grid0 = kv_grid_origin(a.kv_begin, a.kv.n, BNK);
@@ -810,8 +842,8 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
     float* vdst;
     bool accumulate;
     if (a.n_split > 1) {
-      const int64_t plane = (int64_t)gridDim.z * gridDim.y * a.nkeys_pad * D;          // one of dk / dv of one chunk
-      const int64_t row = (((int64_t)b * gridDim.y + hk) * a.nkeys_pad + (mykey_out - grid0)) * D;
+      const int64_t plane = (int64_t)a.dkdv_items[2] * a.dkdv_items[1] * a.nkeys_pad * D;          // one of dk / dv of one chunk
+      const int64_t row = (((int64_t)b * a.dkdv_items[1] + hk) * a.nkeys_pad + (mykey_out - grid0)) * D;
       kdst = a.part + (int64_t)split * 2 * plane + row;
       vdst = kdst + plane;
       accumulate = false;
@@ -900,10 +932,12 @@ __global__ __launch_bounds__(256) void dq_reduce_kernel(const BwdArgs a, int bat
 
 template <int D, int NW>
 static hipError_t launch_dkdv_t(const BwdArgs& a, int batch, hipStream_t st) {
-  constexpr int BNK = NW * 32;
   if (a.kv_end <= a.kv_begin) return hipSuccess;
-  const int64_t nkeys = a.kv_end - kv_grid_origin(a.kv_begin, a.kv.n, BNK);
-  dim3 grid((unsigned)((nkeys + BNK - 1) / BNK) * (unsigned)a.n_split, a.n_kv_heads, batch), block(NW * 64);
+  const int64_t items = (int64_t)a.dkdv_items[0] * a.dkdv_items[1] * a.dkdv_items[2];
+  // with a ticket counter: a quarter more workgroups than items (an XCD that is 10 % faster than the others takes
+  // 10 % more than its eighth of the items; the surplus workgroups take a ticket, see that the items are gone and leave)
+  const int64_t wgs = a.ticket ? items + items / 4 + 64 : items;
+  dim3 grid((unsigned)wgs), block(NW * 64);
   constexpr size_t smem = DkdvLds<D, NW>::TOTAL;
   hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, NW>), grid, block, smem, st, a);
   return hipGetLastError();

@@ -37,6 +37,11 @@ struct FwdArgs {
   int32_t n_ranges;                                   // >= 1; blockIdx.z = batch index * n_ranges + range
   int64_t range_begin[kMaxRanges], range_end[kMaxRanges];
   int64_t out_range_stride, lse_range_stride;         // in elements of the output type / floats
+  // work items = (query block, q head, batch index x range), items[0] * [1] * [2] of them; with `ticket` (a counter
+  // set to zero before the launch) the grid holds more workgroups than items and each takes the next item from the
+  // counter (see BwdArgs::ticket); nullptr: workgroup index = item
+  unsigned* ticket;
+  int32_t items[3];
   int64_t q_offset, kv_capacity;
   float scale_log2e;
   int64_t q_stride_b, q_stride_s, q_stride_h;
@@ -67,6 +72,14 @@ struct BwdArgs {
   int32_t dq_final_f32, dq_final_accumulate;
   int32_t n_split;         // chunks the query stream of a key tile is cut into (one workgroup each)
   int64_t nkeys_pad;       // key rows per (batch, kv head) plane of `part`
+  // dk/dv work items = (key tile x chunk, kv head, batch index), dkdv_items[0] * [1] * [2] of them.  With `ticket`
+  // (a counter in the workspace that the delta kernel sets to zero) the launch has more workgroups than items and
+  // every workgroup takes the next item from the counter instead of deriving it from its index: the hardware hands
+  // workgroups to the eight XCDs round-robin whatever their speed, and this lets a faster XCD take more items.
+  // nullptr: workgroup index = item.
+  unsigned* ticket;         // ticket[0]: dk/dv kernel, ticket[1]: dq kernel
+  int32_t dkdv_items[3];
+  int32_t dq_items[3];      // dq work items = (query block, q head, batch index x key range), handed out the same way
   int32_t s_q, n_q_heads, n_kv_heads, group, causal;
   int32_t dq_f32, dq_accumulate, dkv_accumulate;
   int64_t q_offset, kv_begin, kv_end, kv_capacity;
@@ -94,6 +107,7 @@ hipError_t opt_in_fwd_kernels();
 hipError_t opt_in_bwd_kernels();
 
 hipError_t launch_fwd(const FwdArgs& a, int batch, int head_dim, hipStream_t st);
+hipError_t launch_zero_counter(unsigned* counter, hipStream_t st);
 hipError_t launch_delta(const BwdArgs& a, int batch, int head_dim, hipStream_t st);
 hipError_t launch_bwd_dq(const BwdArgs& a, int batch, int head_dim, hipStream_t st);
 hipError_t launch_bwd_dkdv(const BwdArgs& a, int batch, int head_dim, hipStream_t st);

@@ -319,7 +319,7 @@ def test_redistribution_key_ranges_in_one_launch(sp):
         kk, vv = k[:, :kv_end], v[:, :kv_end]
         out = torch.empty((1, s, Hq, D), device="cuda:0", dtype=torch.bfloat16)
         need = sp.slimpipe_attn_workspace_bytes(sp.make_params(q, kk, out, i * s, 0, kv_end, True, scale), False)
-        assert need > 0
+        assert need > 256          # more than the ticket counter: room for key ranges
         ws = torch.empty(need, device="cuda:0", dtype=torch.uint8)
         say("redistribution slice %d: forward cut into key ranges (workspace %d bytes)" % (i, need))
         o_r, l_r = sp.slimpipe_attn_fwd(q, kk, vv, i * s, 0, kv_end, True, scale, out=out, workspace=ws)

@@ -71,12 +71,13 @@ def test_short_slice_over_long_cache_is_cut_into_ranges():
     p = sp.make_params(q, k, out, q_off, kv_begin, kv_end, True, scale)
     need = sp.slimpipe_attn_workspace_bytes(p, False)
     per_range = B * s * Hq * D * 4 + B * Hq * s * 4
-    assert need > 0 and need % per_range == 0, "8 workgroups on 256 compute units: the call is meant to ask for ranges"
-    say("auto ranges: workspace %d bytes = %d ranges" % (need, need // per_range))
+    ticket = 256          # the workspace starts with the counter the workgroups take their work items from
+    assert need > ticket and (need - ticket) % per_range == 0, "8 workgroups on 256 compute units: the call is meant to ask for ranges"
+    say("auto ranges: workspace %d bytes = counter + %d ranges" % (need, (need - ticket) // per_range))
     o_ref, l_ref = attn_fwd(q64, k64, v64, q_off, kv_begin, kv_end, True, scale)
     o0, l0 = sp.slimpipe_attn_fwd(q, k, v, q_off, kv_begin, kv_end, True, scale)
     res = []
-    for nbytes in (need, need, 2 * per_range, per_range):
+    for nbytes in (need, need, ticket + 2 * per_range, ticket + per_range):
         ws = torch.full((nbytes,), 0xff, device="cuda:0", dtype=torch.uint8)       # NaN patterns: nothing stale may be read
         o, l = sp.slimpipe_attn_fwd(q, k, v, q_off, kv_begin, kv_end, True, scale, workspace=ws)
         torch.cuda.synchronize()

@@ -74,9 +74,9 @@ def test_validation_codes(sp):
 
 def test_workspace_bytes_and_null_pointer_errors(sp):
     p = good_params(sp)
-    assert sp.slimpipe_attn_workspace_bytes(p, False) == 0
+    assert sp.slimpipe_attn_workspace_bytes(p, False) == 256          # the ticket counter, no key ranges for this shape
     n = sp.slimpipe_attn_workspace_bytes(p, True)
-    assert n >= 2 * 4 * 8 * 512 and n % 256 == 0
+    assert n >= 2 * 4 * 8 * 512 + 256 and n % 256 == 0
     # NULL data pointers are refused before anything touches the device
     rc = sp.lib.slimpipe_attn_fwd(ctypes.byref(p), None, None, None, None, None, None, 0, None)
     assert rc == -1
@@ -113,13 +113,14 @@ def test_forward_workspace_asks_for_key_ranges_only_when_the_launch_is_small(sp)
         k = types.SimpleNamespace(shape=(1, kv_end, Hkv, D), stride=lambda i, st=(kv_end * Hkv * D, Hkv * D, D, 1): st[i])
         return sp.make_params(q, k, q, q_off, 0, kv_end, True, None)
     per_range = lambda s, Hq: s * Hq * D * 4 + Hq * s * 4
+    ticket = 256          # every forward workspace starts with the counter the workgroups take their items from
     # the benchmark shape: 64 query blocks x 8 heads = two full rounds on 256 compute units, nothing to gain
-    assert sp.slimpipe_attn_workspace_bytes(params(16384, 8, 1, 15 * 16384, 16 * 16384), False) == 0
+    assert sp.slimpipe_attn_workspace_bytes(params(16384, 8, 1, 15 * 16384, 16 * 16384), False) == ticket
     # 4096-row slices of the redistribution workload: 128 workgroups, two ranges fill the GPU
-    assert sp.slimpipe_attn_workspace_bytes(params(4096, 8, 1, 31 * 4096, 32 * 4096), False) == 2 * per_range(4096, 8)
+    assert sp.slimpipe_attn_workspace_bytes(params(4096, 8, 1, 31 * 4096, 32 * 4096), False) == ticket + 2 * per_range(4096, 8)
     # ... but never ranges shorter than 1024 keys
-    assert sp.slimpipe_attn_workspace_bytes(params(256, 8, 1, 1024, 1280), False) == 0
-    assert sp.slimpipe_attn_workspace_bytes(params(256, 1, 1, 8192 - 256, 8192), False) == 8 * per_range(256, 1)
+    assert sp.slimpipe_attn_workspace_bytes(params(256, 8, 1, 1024, 1280), False) == ticket
+    assert sp.slimpipe_attn_workspace_bytes(params(256, 1, 1, 8192 - 256, 8192), False) == ticket + 8 * per_range(256, 1)
     # more ranges than 16 are refused, as are ranges outside the cache
     p = params(256, 8, 1, 1024, 1280)
     b, e = (ctypes.c_int64 * 17)(*([0] * 17)), (ctypes.c_int64 * 17)(*([64] * 17))
