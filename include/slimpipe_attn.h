@@ -143,18 +143,19 @@ int slimpipe_attn_bwd(const slimpipe_attn_params* p,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* slimpipe_attn_bwd for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
- * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and kernels as
- * slimpipe_attn_bwd given a workspace of the minimum size (the dk/dv query stream is not split, dq is not cut
- * into key ranges), but the two row-statistic arrays the kernels exchange (delta and lse in log2 units, one float
- * each per (batch, q head, row)) live in a fixed 4 MiB array in device memory that belongs to the library, one
- * copy per GPU, held until the process ends.  The call allocates nothing (no hipMalloc / hipFree, no events) and
- * does not synchronise.
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and kernels as slimpipe_attn_bwd,
+ * and bit for bit the results it gives with a workspace of the minimum size (the dk/dv query stream is not split,
+ * dq is not cut into key ranges), but what the kernels exchange - the two row-statistic arrays (delta and lse in
+ * log2 units, one float each per (batch, q head, row)) and the 256-byte counter through which workgroups take their
+ * work items - lives in a fixed array of 4 MiB + 256 bytes in device memory that belongs to the library, one copy per
+ * GPU, held until the process ends.  The call allocates nothing (no hipMalloc / hipFree, no events) and does not
+ * synchronise.
  *   limit : batch * n_q_heads * s_q <= slimpipe_attn_noalloc_max_rows() = 524288, each array rounded up to 256
  *           bytes; beyond that SLIMPIPE_ETOOLARGE is returned and nothing is launched.
- *   The array keeps the last call's contents; every call overwrites the entries it reads (nothing has to start at
- *   zero).  All calls on one GPU share it: two calls whose kernels may overlap on one GPU (different streams, or
- *   host threads) race - serialise them, or use slimpipe_attn_bwd with a workspace each.  Graph capture:
- *   call slimpipe_attn_init() before the capture begins. */
+ *   The array keeps the last call's contents; every call overwrites the entries it reads and sets the counter to
+ *   zero itself (nothing has to start at zero).  All calls on one GPU share it: two calls whose kernels may overlap
+ *   on one GPU (different streams, or host threads) race - serialise them, or use slimpipe_attn_bwd with a
+ *   workspace each.  Graph capture: call slimpipe_attn_init() before the capture begins. */
 int slimpipe_attn_bwd_noalloc(const slimpipe_attn_params* p,
                               const void* q_slice, const void* k_prefix, const void* v_prefix,
                               const void* out, const void* d_out, const float* lse,

@@ -16,8 +16,9 @@ using namespace slimpipe;
 // statistics live here instead of in a caller's workspace.  Every GPU the library runs on holds its own copy
 // until the process ends.  Host code never uses this name as an address: it asks the runtime for the device
 // address once per device (ensure_device_ready) and passes that pointer to the kernels.
-constexpr size_t kScratchBytes = (size_t)4 << 20;
-static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr size_t kScratchBytes = (size_t)4 << 20;          // the two statistics arrays
+constexpr size_t kScratchTicketBytes = 256;                // + the counter the workgroups take their work items from
+static __device__ __align__(256) unsigned char scratch[kScratchBytes + kScratchTicketBytes];
 
 namespace {
 
@@ -97,9 +98,10 @@ int preferred_split(const slimpipe_attn_params* p, int n_chunks, bool ticket) {
     if (cost[i] <= best * 1.03) split = 1 << i;
   // Items handed out through a counter: a compute unit that finishes early takes another one, so more items even out
   // compute units (and XCDs) of unequal speed and key tiles of unequal streams (the causal diagonal).  Up to about 16
-  // items per compute unit, as long as a chunk keeps at least 128 query tiles.
+  // items per compute unit, as long as a chunk keeps at least 512 query tiles (a workgroup's prologue and epilogue
+  // cost about 8 tiles' time, and every chunk adds a plane of partial sums to the reduce kernel's work).
   if (ticket)
-    while (split < 8 && w * split < 16 * (int64_t)cus && stream / (2 * split) >= 128) split *= 2;
+    while (split < 8 && w * split < 16 * (int64_t)cus && stream / (2 * split) >= 512) split *= 2;
   return split;
 }
 // room for the ticket counter of the dk/dv kernel behind the two statistics arrays
@@ -540,10 +542,11 @@ int slimpipe_attn_bwd_noalloc(const slimpipe_attn_params* p, const void* q_slice
   if (delta_bytes(p) > kScratchBytes) return SLIMPIPE_ETOOLARGE;
   void* ws = nullptr;
   if (ensure_device_ready(&ws) != SLIMPIPE_OK || !ws) return SLIMPIPE_ELAUNCH;
-  // exactly the two statistics arrays: no split of the dk/dv query stream, no key ranges for dq (the plan of
-  // slimpipe_attn_bwd given a workspace of the minimum size), and no event records of the benchmark switch
+  // the two statistics arrays and the ticket counter behind them: no split of the dk/dv query stream, no key ranges for
+  // dq (the sums of slimpipe_attn_bwd given a workspace of the minimum size), and no event records of the benchmark switch
+  static_assert(kScratchTicketBytes == kTicketBytes, "the counter sits right behind the statistics");
   return bwd_impl(p, q_slice, &k_prefix, &v_prefix, 1, p->kv_capacity > 0 ? p->kv_capacity : 1, out, d_out, lse, dq, dq_dtype,
-                  dq_accumulate, &dk_acc, &dv_acc, dkv_accumulate, ws, delta_bytes(p), hip_stream, false);
+                  dq_accumulate, &dk_acc, &dv_acc, dkv_accumulate, ws, delta_bytes(p) + kTicketBytes, hip_stream, false);
 }
 
 int slimpipe_attn_noalloc_max_rows(void) { return (int)(kScratchBytes / (2 * sizeof(float))); }
