@@ -345,11 +345,13 @@ static int fwd_impl(const slimpipe_attn_params* p, const void* q_slice, const vo
     a.out_range_stride = 0; a.lse_range_stride = 0;
     a.o_stride_b = p->o_stride_b; a.o_stride_s = p->o_stride_s; a.o_stride_h = p->o_stride_h;
   }
-  a.ticket = ticket;
   a.items[0] = (p->s_q + 255) / 256;
   a.items[1] = p->n_q_heads;
   a.items[2] = p->batch * n_ranges;
   if ((int64_t)a.items[0] * a.items[1] * a.items[2] > (int64_t)1 << 30) return SLIMPIPE_EINVAL_SHAPE;
+  // a counter only where there are more items than compute units (otherwise every workgroup starts at once)
+  if ((int64_t)a.items[0] * a.items[1] * a.items[2] <= compute_units()) ticket = nullptr;
+  a.ticket = ticket;
   if (ensure_device_ready() != SLIMPIPE_OK) return SLIMPIPE_ELAUNCH;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   if (ticket && launch_zero_counter(ticket, st) != hipSuccess) return SLIMPIPE_ELAUNCH;
@@ -466,7 +468,7 @@ static int bwd_impl(const slimpipe_attn_params* p, const void* q_slice, const vo
   // of a split query stream, the partial dq of key ranges
   const bool ticket = workspace_bytes >= delta_bytes(p) + kTicketBytes;
   const size_t fixed = delta_bytes(p) + (ticket ? kTicketBytes : 0);
-  a.ticket = ticket ? reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + delta_bytes(p)) : nullptr;
+  unsigned* const counters = ticket ? reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + delta_bytes(p)) : nullptr;
   int split = preferred_split(p, n_chunks, ticket);
   while (split > 1 && fixed + split_bytes(p, n_chunks, split) > workspace_bytes) split /= 2;
   a.n_split = split;
@@ -498,6 +500,10 @@ static int bwd_impl(const slimpipe_attn_params* p, const void* q_slice, const vo
   a.dq_items[1] = p->n_q_heads;
   a.dq_items[2] = p->batch * dq_ranges;
   if ((int64_t)a.dq_items[0] * a.dq_items[1] * a.dq_items[2] > (int64_t)1 << 30) return SLIMPIPE_EINVAL_SHAPE;
+  // a counter only where there are more items than compute units (otherwise every workgroup starts at once)
+  const int64_t cus = compute_units();
+  a.ticket_dkdv = (counters && (int64_t)a.dkdv_items[0] * a.dkdv_items[1] * a.dkdv_items[2] > cus) ? counters : nullptr;
+  a.ticket_dq = (counters && (int64_t)a.dq_items[0] * a.dq_items[1] * a.dq_items[2] > cus) ? counters + 1 : nullptr;
   if ((int64_t)a.dkdv_items[0] * a.dkdv_items[1] * a.dkdv_items[2] > (int64_t)1 << 30) return SLIMPIPE_EINVAL_SHAPE;
   a.s_q = p->s_q; a.n_q_heads = p->n_q_heads; a.n_kv_heads = p->n_kv_heads;
   a.group = p->n_q_heads / p->n_kv_heads; a.causal = p->causal;

@@ -26,7 +26,10 @@ template <int D>
 __global__ __launch_bounds__(256) void attn_delta_kernel(const BwdArgs a, int batch) {
   constexpr int NC = D / 8;
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (gid == 0 && a.ticket) { a.ticket[0] = 0u; a.ticket[1] = 0u; }     // the dk/dv and dq kernels of this call, later on the stream, count from zero
+  if (gid == 0) {     // the dq and dk/dv kernels of this call, later on the stream, count from zero
+    if (a.ticket_dq) *a.ticket_dq = 0u;
+    if (a.ticket_dkdv) *a.ticket_dkdv = 0u;
+  }
   const int64_t rh = gid / NC;                 // (b, r, h) flattened
   const int c = (int)(gid % NC);
   const int64_t total = (int64_t)batch * a.s_q * a.n_q_heads;
@@ -212,9 +215,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dq_kernel(const BwdArgs a) {
   // Work item: index -> (query block, q head, batch index x key range), the first fastest: the workgroup's own
   // index, or the next value of the ticket counter (surplus workgroups leave at once).
   int item = blockIdx.x;
-  if (a.ticket) {
+  if (a.ticket_dq) {
     unsigned* slot = reinterpret_cast<unsigned*>(smem);      // (the tile rings are not in use yet)
-    if (threadIdx.x == 0) *slot = atomicAdd(a.ticket + 1, 1u);
+    if (threadIdx.x == 0) *slot = atomicAdd(a.ticket_dq, 1u);
     __syncthreads();
     item = (int)*slot;
     __syncthreads();
@@ -392,7 +395,7 @@ static hipError_t launch_dq_t(const BwdArgs& a, int batch, hipStream_t st) {
   constexpr int BM = NW * 32;
   static_assert(BM == 256 && BN == kDqKeysPerTile, "dq_lds_bytes assumes this shape");
   const int64_t items = (int64_t)a.dq_items[0] * a.dq_items[1] * a.dq_items[2];
-  const int64_t wgs = a.ticket ? items + items / 4 + 64 : items;      // (see launch_dkdv_t)
+  const int64_t wgs = a.ticket_dq ? items + items / 4 + 64 : items;      // (see launch_dkdv_t)
   dim3 grid((unsigned)wgs), block(NW * 64);
   hipLaunchKernelGGL((attn_bwd_dq_kernel<D, NW, BN>), grid, block, dq_lds_bytes<D>(), st, a);
   return hipGetLastError();
@@ -579,9 +582,9 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
   // fastest.  Either the workgroup's own index, or the next value of the ticket counter (then the grid holds more
   // workgroups than items and the surplus ones leave at once).
   int item = blockIdx.x;
-  if (a.ticket) {
+  if (a.ticket_dkdv) {
     unsigned* slot = reinterpret_cast<unsigned*>(smem);      // (the tile rings are not in use yet)
-    if (threadIdx.x == 0) *slot = atomicAdd(a.ticket, 1u);
+    if (threadIdx.x == 0) *slot = atomicAdd(a.ticket_dkdv, 1u);
     __syncthreads();
     item = (int)*slot;
     __syncthreads();
@@ -936,7 +939,7 @@ static hipError_t launch_dkdv_t(const BwdArgs& a, int batch, hipStream_t st) {
   const int64_t items = (int64_t)a.dkdv_items[0] * a.dkdv_items[1] * a.dkdv_items[2];
   // with a ticket counter: a quarter more workgroups than items (an XCD that is 10 % faster than the others takes
   // 10 % more than its eighth of the items; the surplus workgroups take a ticket, see that the items are gone and leave)
-  const int64_t wgs = a.ticket ? items + items / 4 + 64 : items;
+  const int64_t wgs = a.ticket_dkdv ? items + items / 4 + 64 : items;
   dim3 grid((unsigned)wgs), block(NW * 64);
   constexpr size_t smem = DkdvLds<D, NW>::TOTAL;
   hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, NW>), grid, block, smem, st, a);

@@ -76,8 +76,10 @@ struct BwdArgs {
   // (a counter in the workspace that the delta kernel sets to zero) the launch has more workgroups than items and
   // every workgroup takes the next item from the counter instead of deriving it from its index: the hardware hands
   // workgroups to the eight XCDs round-robin whatever their speed, and this lets a faster XCD take more items.
-  // nullptr: workgroup index = item.
-  unsigned* ticket;         // ticket[0]: dk/dv kernel, ticket[1]: dq kernel
+  // nullptr: workgroup index = item (no room for the counter in the workspace, or no more items than compute units:
+  // then every workgroup starts at once and there is nothing to even out).
+  unsigned* ticket_dkdv;
+  unsigned* ticket_dq;
   int32_t dkdv_items[3];
   int32_t dq_items[3];      // dq work items = (query block, q head, batch index x key range), handed out the same way
   int32_t s_q, n_q_heads, n_kv_heads, group, causal;
