@@ -97,11 +97,11 @@ int preferred_split(const slimpipe_attn_params* p, int n_chunks, bool ticket) {
   for (int i = 3; i >= 0; --i)
     if (cost[i] <= best * 1.03) split = 1 << i;
   // Items handed out through a counter: a compute unit that finishes early takes another one, so more items even out
-  // compute units (and XCDs) of unequal speed and key tiles of unequal streams (the causal diagonal).  Up to about 16
+  // compute units (and XCDs) of unequal speed and key tiles of unequal streams (the causal diagonal).  Up to about 8
   // items per compute unit, as long as a chunk keeps at least 512 query tiles (a workgroup's prologue and epilogue
   // cost about 8 tiles' time, and every chunk adds a plane of partial sums to the reduce kernel's work).
   if (ticket)
-    while (split < 8 && w * split < 16 * (int64_t)cus && stream / (2 * split) >= 512) split *= 2;
+    while (split < 8 && w * split < 8 * (int64_t)cus && stream / (2 * split) >= 512) split *= 2;
   return split;
 }
 // room for the ticket counter of the dk/dv kernel behind the two statistics arrays
