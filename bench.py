@@ -231,6 +231,12 @@ def main():
         "ms_per_step_with_event_bracketing": round(ms_per_step_pass2, 3),
     }
 
+    # the HBM-bound companions, against the 8 TB/s roof: algorithmic bytes over HIP-event time.  delta reads dO and out
+    # (bf16) and writes one float per row and head; finalize reads the fp32 dK/dV accumulators and writes bf16
+    aux_bytes = {"delta": nrun * s * Hq * (2 * D * 2 + 4.0), "finalize": 2 * N * Hkv * D * 6.0}
+    roofline["hbm_bound_kernels_GBps"] = {kk: round(b * args.steps / (prof[kk][0] * 1e-3) / 1e9, 1)
+                                          for kk, b in aux_bytes.items() if prof[kk][0] > 0}
+
     # what a pure stream of the same MFMA instruction sustains on this GPU (after the timed region): with
     # random operands the chip is power limited, which is the regime the attention kernels run in
     roofline["mfma_stream_tflops"] = {"constant_operands": round(sp.slimpipe_attn_mfma_rate(False), 1),
