@@ -46,7 +46,9 @@ typedef enum slimpipe_status {
   SLIMPIPE_OK = 0,
   SLIMPIPE_EINVAL_NULL = -1,      /* a required pointer is NULL                                   */
   SLIMPIPE_EINVAL_SHAPE = -2,     /* batch/s_q/heads <= 0, Hq % Hkv != 0, head_dim not 64 or 128,  */
-                                  /* scale not finite or <= 0, bad dtype code, n_parts out of range*/
+                                  /* scale not finite or <= 0, bad dtype code, n_parts out of range,*/
+                                  /* batch or n_q_heads > 65535, more than 2^30 work items a launch */
+                                  /* (ceil(s_q / 256) * n_q_heads * batch * key ranges)             */
   SLIMPIPE_EINVAL_RANGE = -3,     /* kv_begin > kv_end, kv_end > kv_capacity, negative offsets     */
   SLIMPIPE_EINVAL_STRIDE = -4,    /* a stride is not a positive multiple of 8 elements             */
   SLIMPIPE_EINVAL_ALIGN = -5,     /* a pointer is not 16-byte aligned                              */

@@ -258,7 +258,7 @@ int slimpipe_attn_validate(const slimpipe_attn_params* p, int is_bwd) {
   if (!(p->scale > 0.0f) || !isfinite(p->scale)) return SLIMPIPE_EINVAL_SHAPE;
   if (p->causal != 0 && p->causal != 1) return SLIMPIPE_EINVAL_SHAPE;
   if (p->out_dtype != SLIMPIPE_BF16 && p->out_dtype != SLIMPIPE_F32) return SLIMPIPE_EINVAL_SHAPE;
-  if (p->batch > 65535 || p->n_q_heads > 65535) return SLIMPIPE_EINVAL_SHAPE;   /* grid y/z limits */
+  if (p->batch > 65535 || p->n_q_heads > 65535) return SLIMPIPE_EINVAL_SHAPE;   /* limits stated in the header */
   if (p->kv_capacity < 0 || p->q_offset < 0 || p->kv_begin < 0) return SLIMPIPE_EINVAL_RANGE;
   if (p->kv_begin > p->kv_end || p->kv_end > p->kv_capacity) return SLIMPIPE_EINVAL_RANGE;
   if (p->q_offset > (int64_t)1 << 40 || p->kv_capacity > (int64_t)1 << 40) return SLIMPIPE_EINVAL_RANGE;

@@ -34,7 +34,7 @@ struct FwdArgs {
   void* out;
   float* lse;
   int32_t s_q, n_q_heads, group, causal, out_f32;
-  int32_t n_ranges;                                   // >= 1; blockIdx.z = batch index * n_ranges + range
+  int32_t n_ranges;                                   // >= 1; third item coordinate = batch index * n_ranges + range
   int64_t range_begin[kMaxRanges], range_end[kMaxRanges];
   int64_t out_range_stride, lse_range_stride;         // in elements of the output type / floats
   // work items = (query block, q head, batch index x range), items[0] * [1] * [2] of them; with `ticket` (a counter
@@ -61,7 +61,7 @@ struct BwdArgs {
   float* dk_acc[kMaxChunks];   // float32 accumulators, chunked like the keys / values
   float* dv_acc[kMaxChunks];
   float* part;             // workspace [n_split][2][batch][n_kv_heads][nkeys_pad][head_dim]: partial dk, dv (n_split > 1)
-  // dq kernel: key ranges of one launch (blockIdx.z = batch index * n_dq_ranges + range).  With one range dq is the
+  // dq kernel: key ranges of one launch (third item coordinate = batch index * n_dq_ranges + range).  With one range dq is the
   // caller's buffer; with several it is the float32 workspace [range][batch, s_q, heads, head_dim] that
   // dq_reduce_kernel adds up into dq_final.
   int32_t n_dq_ranges;
