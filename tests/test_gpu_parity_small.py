@@ -216,6 +216,44 @@ def test_dkdv_bit_reproducible(sp):
         assert torch.equal(r[0], res[0][0]) and torch.equal(r[1], res[0][1]) and torch.equal(r[2], res[0][2])
 
 
+def test_more_work_items_than_compute_units_d64(sp):
+    """head_dim 64 at a size where all three attention kernels have more work items than the GPU has compute units, so
+    that workgroups take their items from the counter in the workspace:
+    every element against the oracle, and two runs bit-equal although workgroups and items pair up differently."""
+    import torch
+    B, s, Hq, Hkv, D, q_off = 1, 1100, 56, 56, 64, 256
+    Nkv = q_off + s
+    scale = 1.0 / math.sqrt(D)
+    qb, kb, vb, dob = normal_bf16((B, s, Hq, D), 11, "q"), normal_bf16((B, Nkv, Hkv, D), 11, "k"), normal_bf16((B, Nkv, Hkv, D), 11, "v"), normal_bf16((B, s, Hq, D), 11, "do")
+    q64, k64, v64, do64 = (bf16_bits_to_f64(x) for x in (qb, kb, vb, dob))
+    q, k, v, do = dev_bf16(qb), dev_bf16(kb), dev_bf16(vb), dev_bf16(dob)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert (s + 255) // 256 * Hq * B > cus and (Nkv + 255) // 256 * Hkv * B > cus, "this shape is meant to exceed the compute units"
+    p = sp.make_params(q, k, q, q_off, 0, Nkv, True, scale)
+    fws = torch.empty(sp.slimpipe_attn_workspace_bytes(p, False), device="cuda:0", dtype=torch.uint8)
+    bws = torch.empty(sp.slimpipe_attn_workspace_bytes(p, True), device="cuda:0", dtype=torch.uint8)
+    runs = []
+    for rep in range(2):
+        say("more items than compute units, D 64: run %d" % rep)
+        o, l = sp.slimpipe_attn_fwd(q, k, v, q_off, 0, Nkv, True, scale, workspace=fws)
+        dk_acc = torch.zeros((B, Nkv, Hkv, D), device="cuda:0")
+        dv_acc = torch.zeros_like(dk_acc)
+        dq = sp.slimpipe_attn_bwd(q, k, v, o, do, l, q_off, 0, Nkv, dk_acc, dv_acc, True, scale, dq_dtype=sp.F32,
+                                  dkv_accumulate=False, workspace=bws)
+        torch.cuda.synchronize()
+        runs.append((o, l, dq, dk_acc, dv_acc))
+    for a, b in zip(runs[0], runs[1]):
+        assert torch.equal(a, b)
+    o, l, dq, dk_acc, dv_acc = runs[0]
+    say("oracle")
+    o_ref, l_ref = attn_fwd(q64, k64, v64, q_off, 0, Nkv, True, scale)
+    check_fwd("D 64, counter-driven forward", o, l, o_ref, l_ref)
+    dq_r, dk_r, dv_r = attn_bwd(q64, k64, v64, o_ref, do64, l_ref, q_off, 0, Nkv, True, scale)
+    check_grad("D 64, counter-driven dq, oracle-only chain", dq, dq_r)
+    check_grad("D 64, counter-driven dk, oracle-only chain", dk_acc, dk_r)
+    check_grad("D 64, counter-driven dv, oracle-only chain", dv_acc, dv_r)
+
+
 def test_dkdv_split_query_stream(sp):
     """Few key tiles and a long query stream: the dk/dv kernel cuts the stream of every key tile into
     chunks (partial sums + reduce kernel).  Checked against the oracle, against the unsplit path
