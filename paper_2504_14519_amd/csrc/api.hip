@@ -100,8 +100,12 @@ int preferred_split(const slimpipe_attn_params* p, int n_chunks, bool ticket) {
   // compute units (and XCDs) of unequal speed and key tiles of unequal streams (the causal diagonal).  Up to about 8
   // items per compute unit, as long as a chunk keeps at least 512 query tiles (a workgroup's prologue and epilogue
   // cost about 8 tiles' time, and every chunk adds a plane of partial sums to the reduce kernel's work).
-  if (ticket)
+  // And no split for the sake of whole rounds once there are two items per compute unit anyway: the counter evens out
+  // most of what the rounding would cost, and the partial sums with their reduce kernel cost more than the rest.
+  if (ticket) {
+    if (w >= 2 * (int64_t)cus) split = 1;
     while (split < 8 && w * split < 8 * (int64_t)cus && stream / (2 * split) >= 512) split *= 2;
+  }
   return split;
 }
 // room for the ticket counter of the dk/dv kernel behind the two statistics arrays
@@ -502,6 +506,7 @@ static int bwd_impl(const slimpipe_attn_params* p, const void* q_slice, const vo
   if ((int64_t)a.dq_items[0] * a.dq_items[1] * a.dq_items[2] > (int64_t)1 << 30) return SLIMPIPE_EINVAL_SHAPE;
   // a counter only where there are more items than compute units (otherwise every workgroup starts at once)
   const int64_t cus = compute_units();
+  a.dkdv_wgs = (int32_t)cus;
   a.ticket_dkdv = (counters && (int64_t)a.dkdv_items[0] * a.dkdv_items[1] * a.dkdv_items[2] > cus) ? counters : nullptr;
   a.ticket_dq = (counters && (int64_t)a.dq_items[0] * a.dq_items[1] * a.dq_items[2] > cus) ? counters + 1 : nullptr;
   if ((int64_t)a.dkdv_items[0] * a.dkdv_items[1] * a.dkdv_items[2] > (int64_t)1 << 30) return SLIMPIPE_EINVAL_SHAPE;

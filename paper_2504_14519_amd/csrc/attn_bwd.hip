@@ -566,30 +566,19 @@ SP_DEV void dkdv_vector_phase(DkdvState<D>& st, const float* stat, float c, bool
 
 static_assert((DkdvLds<128, 8>::SLOTS & (DkdvLds<128, 8>::SLOTS - 1)) == 0, "ring slots are stepped with a mask");
 
+// One work item: index -> (key tile * n_split + chunk of that tile's query stream, kv head, batch index), the first
+// fastest.
 template <int D, int NW>
-__global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a) {
+SP_DEV void dkdv_item(const BwdArgs& a, int item, char* smem) {
   static_assert(NW == 8, "two groups of four waves");
   using L = DkdvLds<D, NW>;
   constexpr int BNK = NW * 32, BMQ = L::BMQ, KS = D / 16, DB = D / 32, T = NW * 64, GT = T / 2;
   constexpr int TILE_BYTES = L::TILE_BYTES, SLOTS = L::SLOTS;
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, ql = lane & 31;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);      // known uniform to the compiler
   const bool group_b = wave_u >= NW / 2;
   const int gtid = tid & (GT - 1);
-  // Work item: index -> (key tile * n_split + chunk of that tile's query stream, kv head, batch index), the first
-  // fastest.  Either the workgroup's own index, or the next value of the ticket counter (then the grid holds more
-  // workgroups than items and the surplus ones leave at once).
-  int item = blockIdx.x;
-  if (a.ticket_dkdv) {
-    unsigned* slot = reinterpret_cast<unsigned*>(smem);      // (the tile rings are not in use yet)
-    if (threadIdx.x == 0) *slot = atomicAdd(a.ticket_dkdv, 1u);
-    __syncthreads();
-    item = (int)*slot;
-    __syncthreads();
-    if (item >= a.dkdv_items[0] * a.dkdv_items[1] * a.dkdv_items[2]) return;
-  }
   // (the quotients come out of vector instructions: read them back so that the compiler knows they are uniform)
   item = __builtin_amdgcn_readfirstlane(item);
   const int per_b = a.dkdv_items[0] * a.dkdv_items[1];
@@ -879,6 +868,30 @@ __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a)
   }
 }
 
+// Without a ticket counter the workgroup's index is its one item.  With it (a counter set to zero before the launch),
+// the launch has one workgroup per compute unit and each takes items from the counter until none is left: a compute
+// unit (or XCD) that runs faster does more of them, and an item costs no workgroup dispatch (with one query head per
+// KV head an item is 60 to 120 us of work).  Every workgroup reaches a ticket past the last item and leaves.
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int n_items = a.dkdv_items[0] * a.dkdv_items[1] * a.dkdv_items[2];
+  for (;;) {                                                // (one copy of the item's code for both ways of getting an item)
+    int item = blockIdx.x;
+    if (a.ticket_dkdv) {
+      unsigned* slot = reinterpret_cast<unsigned*>(smem);  // the ticket goes through the first bytes of the tile rings
+      __syncthreads();                                      // every wave is done with the rings of the item before
+      if (threadIdx.x == 0) *slot = atomicAdd(a.ticket_dkdv, 1u);
+      __syncthreads();
+      item = (int)*slot;
+      __syncthreads();                                      // read by all before the first tile copy lands there
+      if (item >= n_items) return;
+    }
+    dkdv_item<D, NW>(a, item, smem);
+    if (!a.ticket_dkdv) return;
+  }
+}
+
 // dk_acc, dv_acc (+)= the partial sums of the chunks, chunk 0 first.
 __global__ __launch_bounds__(256) void dkdv_reduce_kernel(const BwdArgs a, int batch, int head_dim) {
   const int64_t nkeys = a.kv_end - a.kv_begin;
@@ -937,9 +950,8 @@ template <int D, int NW>
 static hipError_t launch_dkdv_t(const BwdArgs& a, int batch, hipStream_t st) {
   if (a.kv_end <= a.kv_begin) return hipSuccess;
   const int64_t items = (int64_t)a.dkdv_items[0] * a.dkdv_items[1] * a.dkdv_items[2];
-  // with a ticket counter: a quarter more workgroups than items (an XCD that is 10 % faster than the others takes
-  // 10 % more than its eighth of the items; the surplus workgroups take a ticket, see that the items are gone and leave)
-  const int64_t wgs = a.ticket_dkdv ? items + items / 4 + 64 : items;
+  // with a ticket counter: one workgroup per compute unit (the kernel's LDS allows one at a time), each looping over items
+  const int64_t wgs = a.ticket_dkdv ? (items < a.dkdv_wgs ? items : a.dkdv_wgs) : items;
   dim3 grid((unsigned)wgs), block(NW * 64);
   constexpr size_t smem = DkdvLds<D, NW>::TOTAL;
   hipLaunchKernelGGL((attn_bwd_dkdv_kernel<D, NW>), grid, block, smem, st, a);

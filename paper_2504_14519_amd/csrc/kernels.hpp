@@ -73,13 +73,15 @@ struct BwdArgs {
   int32_t n_split;         // chunks the query stream of a key tile is cut into (one workgroup each)
   int64_t nkeys_pad;       // key rows per (batch, kv head) plane of `part`
   // dk/dv work items = (key tile x chunk, kv head, batch index), dkdv_items[0] * [1] * [2] of them.  With `ticket`
-  // (a counter in the workspace that the delta kernel sets to zero) the launch has more workgroups than items and
-  // every workgroup takes the next item from the counter instead of deriving it from its index: the hardware hands
-  // workgroups to the eight XCDs round-robin whatever their speed, and this lets a faster XCD take more items.
+  // (a counter in the workspace that the delta kernel sets to zero) workgroups take the next item from the counter
+  // instead of deriving it from their index: the hardware hands workgroups to the eight XCDs round-robin whatever
+  // their speed, and this lets a faster XCD take more items.  The dk/dv launch then has dkdv_wgs workgroups (one per
+  // compute unit) that loop over items; the dq launch has a quarter more workgroups than items, one item each.
   // nullptr: workgroup index = item (no room for the counter in the workspace, or no more items than compute units:
   // then every workgroup starts at once and there is nothing to even out).
   unsigned* ticket_dkdv;
   unsigned* ticket_dq;
+  int32_t dkdv_wgs;
   int32_t dkdv_items[3];
   int32_t dq_items[3];      // dq work items = (query block, q head, batch index x key range), handed out the same way
   int32_t s_q, n_q_heads, n_kv_heads, group, causal;
