@@ -508,7 +508,7 @@ static int bwd_impl(const slimpipe_attn_params* p, const void* q_slice, const vo
   const int64_t cus = compute_units();
   a.dkdv_wgs = (int32_t)cus;
   a.ticket_dkdv = (counters && (int64_t)a.dkdv_items[0] * a.dkdv_items[1] * a.dkdv_items[2] > cus) ? counters : nullptr;
-  a.ticket_dq = (counters && (int64_t)a.dq_items[0] * a.dq_items[1] * a.dq_items[2] > cus) ? counters + 1 : nullptr;
+  a.ticket_dq = (counters && (int64_t)a.dq_items[0] * a.dq_items[1] * a.dq_items[2] > cus) ? counters + 8 : nullptr;     // [0..7]: dk/dv, one per XCD
   if ((int64_t)a.dkdv_items[0] * a.dkdv_items[1] * a.dkdv_items[2] > (int64_t)1 << 30) return SLIMPIPE_EINVAL_SHAPE;
   a.s_q = p->s_q; a.n_q_heads = p->n_q_heads; a.n_kv_heads = p->n_kv_heads;
   a.group = p->n_q_heads / p->n_kv_heads; a.causal = p->causal;

@@ -26,9 +26,9 @@ template <int D>
 __global__ __launch_bounds__(256) void attn_delta_kernel(const BwdArgs a, int batch) {
   constexpr int NC = D / 8;
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (gid == 0) {     // the dq and dk/dv kernels of this call, later on the stream, count from zero
-    if (a.ticket_dq) *a.ticket_dq = 0u;
-    if (a.ticket_dkdv) *a.ticket_dkdv = 0u;
+  if (gid < 8) {      // the dq and dk/dv kernels of this call, later on the stream, count from zero
+    if (gid == 0 && a.ticket_dq) *a.ticket_dq = 0u;
+    if (a.ticket_dkdv) a.ticket_dkdv[gid] = 0u;      // one counter per XCD
   }
   const int64_t rh = gid / NC;                 // (b, r, h) flattened
   const int c = (int)(gid % NC);
@@ -868,24 +868,38 @@ SP_DEV void dkdv_item(const BwdArgs& a, int item, char* smem) {
   }
 }
 
-// Without a ticket counter the workgroup's index is its one item.  With it (a counter set to zero before the launch),
-// the launch has one workgroup per compute unit and each takes items from the counter until none is left: a compute
-// unit (or XCD) that runs faster does more of them, and an item costs no workgroup dispatch (with one query head per
-// KV head an item is 60 to 120 us of work).  Every workgroup reaches a ticket past the last item and leaves.
+// Without ticket counters the workgroup's index is its one item.  With them (set to zero before the launch), the
+// launch has one workgroup per compute unit and each takes items until none is left: a compute unit (or XCD) that runs
+// faster does more of them, and an item costs no workgroup dispatch (with one query head per KV head an item is 60 to
+// 120 us of work).  There is one counter per XCD: the items with index = c (mod 8) form class c, the workgroups of
+// XCD c take class c in order first and move on to the next class when theirs is used up.  Items of one class are the
+// same chunk of the query stream (8 or 4 chunks) for one key tile after the other, so the workgroups that share an
+// L2 walk the same eighth of Q and dO.  A workgroup leaves after it has found all eight classes empty.
 template <int D, int NW>
 __global__ __launch_bounds__(NW * 64) void attn_bwd_dkdv_kernel(const BwdArgs a) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int n_items = a.dkdv_items[0] * a.dkdv_items[1] * a.dkdv_items[2];
+  int cls = (int)(__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 7u);      // XCC_ID
+  int empty = 0;                                            // classes found empty so far
   for (;;) {                                                // (one copy of the item's code for both ways of getting an item)
     int item = blockIdx.x;
     if (a.ticket_dkdv) {
-      unsigned* slot = reinterpret_cast<unsigned*>(smem);  // the ticket goes through the first bytes of the tile rings
+      int* slot = reinterpret_cast<int*>(smem);            // the item goes through the first bytes of the tile rings
       __syncthreads();                                      // every wave is done with the rings of the item before
-      if (threadIdx.x == 0) *slot = atomicAdd(a.ticket_dkdv, 1u);
+      if (threadIdx.x == 0) {
+        int it = -1;
+        while (empty < 8) {
+          const unsigned t = atomicAdd(a.ticket_dkdv + cls, 1u);
+          if ((int64_t)t * 8 + cls < n_items) { it = (int)t * 8 + cls; break; }
+          cls = (cls + 1) & 7;
+          ++empty;
+        }
+        *slot = it;
+      }
       __syncthreads();
-      item = (int)*slot;
+      item = *slot;
       __syncthreads();                                      // read by all before the first tile copy lands there
-      if (item >= n_items) return;
+      if (item < 0) return;
     }
     dkdv_item<D, NW>(a, item, smem);
     if (!a.ticket_dkdv) return;

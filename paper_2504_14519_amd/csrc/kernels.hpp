@@ -76,7 +76,8 @@ struct BwdArgs {
   // (a counter in the workspace that the delta kernel sets to zero) workgroups take the next item from the counter
   // instead of deriving it from their index: the hardware hands workgroups to the eight XCDs round-robin whatever
   // their speed, and this lets a faster XCD take more items.  The dk/dv launch then has dkdv_wgs workgroups (one per
-  // compute unit) that loop over items; the dq launch has a quarter more workgroups than items, one item each.
+  // compute unit) that loop over items, with ticket_dkdv[0..7] one counter per XCD; the dq launch has a quarter more
+  // workgroups than items, one item each, and one counter.
   // nullptr: workgroup index = item (no room for the counter in the workspace, or no more items than compute units:
   // then every workgroup starts at once and there is nothing to even out).
   unsigned* ticket_dkdv;
