@@ -96,12 +96,12 @@ int slimpipe_attn_validate(const slimpipe_attn_params* p, int is_bwd);
  * blocks leave compute units idle, room for the float32 partial (out, lse) of the 2 to 16
  * key ranges of equal work the call is cut into (see slimpipe_attn_fwd).  Backward needs two floats per
  * (batch, q head, row): delta = rowsum(d_out * out) (kept negated) and lse in log2 units, each array rounded up to
- * 256 bytes; slimpipe_attn_bwd refuses less.  On top of that it can use, in this order: 256 bytes for a counter
- * through which the workgroups of the dk/dv kernel take their work items (the hardware hands workgroups to the
- * chip's eight XCDs in turn whatever their speed; with the counter a faster XCD takes more items; the results do
+ * 256 bytes; slimpipe_attn_bwd refuses less.  On top of that it can use, in this order: 256 bytes for the counters
+ * through which the workgroups of the dq and dk/dv kernels take their work items (the hardware hands workgroups to the
+ * chip's eight XCDs in turn whatever their speed; with counters a faster XCD takes more items; the results do
  * not depend on who computes what), and room for partial dk/dv sums: when the key tiles of a call do not fill the
- * GPU's compute units evenly, or when the counter is there and more items make for a more even finish, the query
- * rows of each key tile are cut into 2, 4 or 8 chunks that run as workgroups of their own, each writing float32
+ * GPU's compute units evenly, or when the counters are there and more items make for a more even finish, the query
+ * rows of each key tile are cut into 2, 4 or 8 chunks that run as work items of their own, each writing float32
  * partial sums [chunk][dk, dv][batch][kv head][keys rounded up to 256][head_dim] that a second kernel adds up
  * in chunk order.  The figure returned here includes that room for the split this call would pick;
  * given less, slimpipe_attn_bwd uses the largest split that fits (down to none).  In the same way the dq
