@@ -130,3 +130,32 @@ def test_forward_workspace_asks_for_key_ranges_only_when_the_launch_is_small(sp)
     assert sp.lib.slimpipe_attn_fwd_ranges(*args(0)) == -2
     e[3] = 1281
     assert sp.lib.slimpipe_attn_fwd_ranges(*args(4)) == -3
+
+
+def test_backward_workspace_follows_the_split_policy(sp):
+    """The backward workspace query = statistics + counters + partial dk/dv sums of the split the call would pick
+    (+ partial dq of key ranges): the split policy of the dk/dv kernel, checked without a GPU (256 compute units are
+    assumed when no device can be asked)."""
+    import types
+    D = 128
+    def params(s, Hq, Hkv, q_off, kv_end):
+        q = types.SimpleNamespace(shape=(1, s, Hq, D), stride=lambda i, st=(s * Hq * D, Hq * D, D, 1): st[i])
+        k = types.SimpleNamespace(shape=(1, kv_end, Hkv, D), stride=lambda i, st=(kv_end * Hkv * D, Hkv * D, D, 1): st[i])
+        return sp.make_params(q, k, q, q_off, 0, kv_end, True, None)
+    stats = lambda s, Hq: 2 * ((Hq * s * 4 + 255) // 256 * 256)
+    counters = 256
+    parts = lambda split, Hkv, keys: split * 2 * Hkv * keys * D * 4          # [chunk][dk, dv][kv head][keys][head_dim] floats
+    dq_part = lambda s, Hq: s * Hq * D * 4
+    # the benchmark workload, first slice: 64 key tiles for 256 compute units, streams of 4096 query tiles -> 8 chunks
+    assert sp.slimpipe_attn_workspace_bytes(params(16384, 8, 1, 0, 16384), True) == stats(16384, 8) + counters + parts(8, 1, 16384)
+    # its last slice: 1024 key tiles = 4 per compute unit -> 2 chunks bring them to 8
+    assert sp.slimpipe_attn_workspace_bytes(params(16384, 8, 1, 15 * 16384, 16 * 16384), True) == stats(16384, 8) + counters + parts(2, 1, 16 * 16384)
+    # the longest workload: 4096 key tiles, nothing to cut
+    assert sp.slimpipe_attn_workspace_bytes(params(16384, 8, 1, 63 * 16384, 64 * 16384), True) == stats(16384, 8) + counters
+    # 40 KV heads, 4096-row slices: 640 items of 128 query tiles (2.5 per compute unit): no split for whole rounds
+    # once the counters are there; forward-like key ranges for dq (640 query blocks -> 2 ranges)
+    assert sp.slimpipe_attn_workspace_bytes(params(4096, 40, 40, 0, 4096), True) == stats(4096, 40) + counters + 2 * dq_part(4096, 40)
+    # the redistribution workload's last slice: 512 key tiles = 2 per compute unit, streams of 1024 tiles -> 2 chunks
+    # (none below 512 tiles); dq in two key ranges
+    assert sp.slimpipe_attn_workspace_bytes(params(4096, 8, 1, 31 * 4096, 32 * 4096), True) == \
+        stats(4096, 8) + counters + parts(2, 1, 32 * 4096) + 2 * dq_part(4096, 8)
