@@ -47,7 +47,11 @@ def test_noalloc_backward_matches_workspace_backward_twice():
     import torch
     assert torch.cuda.is_available(), "needs the MI355X"
     import paper_2504_14519_amd as sp
-    # first call: 1024 rows, 8/2 heads, range cutting the diagonal block; second call: smaller in every dimension
+    # first call: more work items than compute units in the dq and the dk/dv kernel, so that the no-alloc path hands
+    # them out through the counters it keeps in the fixed array (the workspace of the minimum size has no room for
+    # counters: there the workgroup index is the item; the bits agree all the same)
+    one_case(sp, 0, 1, 4352, 4608, 16, 16, 64, 256, 0, 4608)
+    # then 1024 rows, 8/2 heads, range cutting the diagonal block; last call: smaller in every dimension
     one_case(sp, 1, 1, 1024, 3072, 8, 2, 128, 2048, 100, 2900)
     one_case(sp, 2, 1, 200, 777, 4, 4, 64, 500, 0, 650)
 
